@@ -1,0 +1,134 @@
+"""CPU oracle for the batched inverse-Helmholtz tensor-product operator.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, the smoke check and the benchmark's
+CPU-baseline leg, never by the product package.  The arithmetic lives in ``tpo_oracle.c``
+(plain C, fp64, left-to-right sums); this module compiles it with gcc and marshals NumPy
+arrays into it.  Inputs of any float dtype are promoted to fp64 first, so an fp32 workload
+is checked against the fp64 result on the same rounded inputs.
+
+Operator and index conventions: see the header of ``tpo_oracle.c`` (Sec. 2.2 and the
+reduction-lifting example of Sec. 5.2 of the paper).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tpo_oracle.c")
+_LIB = os.path.join(_HERE, "libtpo_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ``tpo_oracle.c`` into ``libtpo_oracle.so`` next to it (gcc, -O2, no FMA
+    contraction, OpenMP over elements only)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + f".tmp{os.getpid()}"
+    cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.tpo_oracle_ihelm_lifted.argtypes = [dp, dp, dp, dp, dp, dp, ctypes.c_int,
+                                                ctypes.c_longlong, ctypes.c_int]
+        lib.tpo_oracle_ihelm_lifted.restype = ctypes.c_int
+        lib.tpo_oracle_ihelm_direct.argtypes = [dp, dp, dp, dp, dp, dp, ctypes.c_int,
+                                                ctypes.c_longlong]
+        lib.tpo_oracle_ihelm_direct.restype = ctypes.c_int
+        lib.tpo_oracle_forward_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int,
+                                                  ctypes.c_longlong]
+        lib.tpo_oracle_forward_lifted.restype = ctypes.c_int
+        lib.tpo_oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _check_shapes(u, sx, sy, sz, d):
+    if u.ndim != 4 or not (u.shape[1] == u.shape[2] == u.shape[3]):
+        raise ValueError(f"u must be [E,n,n,n], got {u.shape}")
+    n = u.shape[1] if u.shape[0] else (sx.shape[0] if sx.ndim == 2 else 0)
+    for name, s in (("S_x", sx), ("S_y", sy), ("S_z", sz)):
+        if s.shape != (n, n):
+            raise ValueError(f"{name} must be [{n},{n}], got {s.shape}")
+    if d is not None and d.shape != u.shape:
+        raise ValueError(f"D must have u's shape {u.shape}, got {d.shape}")
+    return n
+
+
+def max_threads() -> int:
+    return int(_load().tpo_oracle_max_threads())
+
+
+def ihelm_apply(u, s_x, s_y, s_z, d, nthreads: int = 0) -> np.ndarray:
+    """``v = (S_x (x) S_y (x) S_z) diag(D) (S_x (x) S_y (x) S_z)^T u`` per element, by the
+    lifted (sum-factorised) form.  Returns fp64 ``[E,n,n,n]``."""
+    u, s_x, s_y, s_z, d = map(_f64, (u, s_x, s_y, s_z, d))
+    n = _check_shapes(u, s_x, s_y, s_z, d)
+    v = np.empty_like(u)
+    rc = _load().tpo_oracle_ihelm_lifted(_ptr(u), _ptr(s_x), _ptr(s_y), _ptr(s_z), _ptr(d),
+                                         _ptr(v), n, u.shape[0], nthreads)
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_ihelm_lifted failed ({rc})")
+    return v
+
+
+def ihelm_apply_direct(u, s_x, s_y, s_z, d) -> np.ndarray:
+    """Same operator by the unlifted six-deep sums (O(n^6) per element; small n only)."""
+    u, s_x, s_y, s_z, d = map(_f64, (u, s_x, s_y, s_z, d))
+    n = _check_shapes(u, s_x, s_y, s_z, d)
+    v = np.empty_like(u)
+    rc = _load().tpo_oracle_ihelm_direct(_ptr(u), _ptr(s_x), _ptr(s_y), _ptr(s_z), _ptr(d),
+                                         _ptr(v), n, u.shape[0])
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_ihelm_direct failed ({rc})")
+    return v
+
+
+def forward(u, s_x, s_y, s_z) -> np.ndarray:
+    """Forward half only: ``t = (S_x^T (x) S_y^T (x) S_z^T) u`` (the worked example of
+    Sec. 5.2), lifted form."""
+    u, s_x, s_y, s_z = map(_f64, (u, s_x, s_y, s_z))
+    n = _check_shapes(u, s_x, s_y, s_z, None)
+    t = np.empty_like(u)
+    rc = _load().tpo_oracle_forward_lifted(_ptr(u), _ptr(s_x), _ptr(s_y), _ptr(s_z),
+                                           _ptr(t), n, u.shape[0])
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_forward_lifted failed ({rc})")
+    return t
+
+
+def max_rel_err_per_element(v_test, v_ref) -> float:
+    """Worst over elements of ``max|v_test - v_ref| / max|v_ref|`` (max-norm relative error
+    per element).  An all-zero reference element counts its absolute error."""
+    a = np.asarray(v_test, dtype=np.float64)
+    b = np.asarray(v_ref, dtype=np.float64)
+    if a.shape != b.shape:
+        raise ValueError("shape mismatch")
+    if a.size == 0:
+        return 0.0
+    e = a.shape[0]
+    num = np.abs(a - b).reshape(e, -1).max(axis=1)
+    den = np.abs(b).reshape(e, -1).max(axis=1)
+    den = np.where(den > 0, den, 1.0)
+    return float((num / den).max())

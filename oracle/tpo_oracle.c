@@ -1,0 +1,187 @@
+/*
+ * CPU oracle for the batched inverse-Helmholtz tensor-product operator.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the operator
+ * computes.  It is linked by nothing in the product library; only the tests, the smoke
+ * check and the benchmark's CPU-baseline leg call it.  It shares no code with the GPU path.
+ *
+ * Operator (per element e, independent of every other element; Sec. 2.2 describes such
+ * tensor-product operators as successive one-dimensional transformations, Sec. 6.1 states
+ * the per-element parallelism):
+ *
+ *   forward   t[i,j,k] = sum_l sum_m sum_q  Sx[l,i] * Sy[m,j] * Sz[q,k] * u[l,m,q]
+ *   scale     g[i,j,k] = D[i,j,k] * t[i,j,k]
+ *   backward  v[i,j,k] = sum_l sum_m sum_q  Sx[i,l] * Sy[j,m] * Sz[k,q] * g[l,m,q]
+ *
+ * i.e. v = (Sx (x) Sy (x) Sz) diag(D) (Sx (x) Sy (x) Sz)^T u on the row-major flattening of
+ * the cube.  The forward half is the worked example of Sec. 5.2 ("reduction lifting"): the
+ * matrix written S^T there is the transpose of the array passed in, so the forward sums
+ * run over the FIRST index of the row-major array and the backward sums over the SECOND.
+ * Indices run 0..p inclusive in the paper, so n = p + 1 points per direction.
+ *
+ * Layout: u, D, v are [E][n][n][n] C-contiguous (axis 2 fastest); Sx, Sy, Sz are [n][n]
+ * row-major and pair with axis 0, 1, 2.
+ *
+ * All arithmetic is IEEE double, accumulated left to right, no blocking, no reordering
+ * beyond what the two forms below state.  Compile with -ffp-contract=off so that no
+ * multiply-add is fused.
+ *
+ * Pins (tests/test_oracle_pins.py): explicit n^3 x n^3 Kronecker matrix, exact rational
+ * evaluation on tiny inputs, orthogonal-S identity, eigenvector property with three
+ * distinct non-symmetric matrices, dense Helmholtz solve, linearity, self-adjointness.
+ */
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define TPO_ORACLE_MAX_N 64
+
+/* One mode product along one axis of an n x n x n cube.
+ *   axis 0: out[i,b,c] = sum_l M(l,i) * in[l,b,c]
+ *   axis 1: out[a,j,c] = sum_m M(m,j) * in[a,m,c]
+ *   axis 2: out[a,b,k] = sum_q M(q,k) * in[a,b,q]
+ * where M(r,o) = S[r*n+o] when transposed != 0 (the forward transform, which applies the
+ * transpose of the stored matrix) and M(r,o) = S[o*n+r] otherwise (the backward one). */
+static void mode_product(const double *S, int transposed, int axis, int n,
+                         const double *in, double *out)
+{
+    for (int a = 0; a < n; ++a)
+        for (int b = 0; b < n; ++b)
+            for (int c = 0; c < n; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < n; ++r) {
+                    int o = (axis == 0) ? a : (axis == 1) ? b : c;
+                    double m = transposed ? S[r * n + o] : S[o * n + r];
+                    size_t src = (axis == 0) ? ((size_t)r * n + b) * n + c
+                               : (axis == 1) ? ((size_t)a * n + r) * n + c
+                                             : ((size_t)a * n + b) * n + r;
+                    acc = acc + m * in[src];
+                }
+                out[((size_t)a * n + b) * n + c] = acc;
+            }
+}
+
+/* Lifted (sum-factorised) form, Sec. 5.2: the innermost sum (fastest axis) is taken first,
+ * then the middle one, then the outermost, for the forward and for the backward half.
+ * Returns 0, or -1 on a bad argument or failed allocation.  nthreads <= 0 means "all". */
+int tpo_oracle_ihelm_lifted(const double *u, const double *Sx, const double *Sy,
+                            const double *Sz, const double *D, double *v, int n,
+                            long long num_elems, int nthreads)
+{
+    if (n < 1 || n > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!u || !Sx || !Sy || !Sz || !D || !v) return -1;
+    const size_t cube = (size_t)n * n * n;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+#pragma omp parallel num_threads(nthreads)
+    {
+        double *p = (double *)malloc(cube * sizeof(double));
+        double *q = (double *)malloc(cube * sizeof(double));
+        if (!p || !q) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(static)
+            for (long long e = 0; e < num_elems; ++e) {
+                const double *ue = u + (size_t)e * cube;
+                const double *De = D + (size_t)e * cube;
+                double *ve = v + (size_t)e * cube;
+                mode_product(Sz, 1, 2, n, ue, p);
+                mode_product(Sy, 1, 1, n, p, q);
+                mode_product(Sx, 1, 0, n, q, p);
+                for (size_t x = 0; x < cube; ++x) q[x] = De[x] * p[x];
+                mode_product(Sz, 0, 2, n, q, p);
+                mode_product(Sy, 0, 1, n, p, q);
+                mode_product(Sx, 0, 0, n, q, ve);
+            }
+        }
+        free(p);
+        free(q);
+    }
+    return failed ? -1 : 0;
+}
+
+/* Unlifted form: the six-deep sums exactly as the definition writes them, O(n^6) per
+ * element.  Serves as the slow cross-check of the lifted form (Sec. 5.2 states the two are
+ * the same sum rearranged by distributivity). */
+int tpo_oracle_ihelm_direct(const double *u, const double *Sx, const double *Sy,
+                            const double *Sz, const double *D, double *v, int n,
+                            long long num_elems)
+{
+    if (n < 1 || n > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!u || !Sx || !Sy || !Sz || !D || !v) return -1;
+    const size_t cube = (size_t)n * n * n;
+    double *g = (double *)malloc(cube * sizeof(double));
+    if (!g) return -1;
+    for (long long e = 0; e < num_elems; ++e) {
+        const double *ue = u + (size_t)e * cube;
+        const double *De = D + (size_t)e * cube;
+        double *ve = v + (size_t)e * cube;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j)
+                for (int k = 0; k < n; ++k) {
+                    double t = 0.0;
+                    for (int l = 0; l < n; ++l)
+                        for (int m = 0; m < n; ++m)
+                            for (int q = 0; q < n; ++q)
+                                t = t + Sx[l * n + i] * Sy[m * n + j] * Sz[q * n + k]
+                                        * ue[((size_t)l * n + m) * n + q];
+                    size_t x = ((size_t)i * n + j) * n + k;
+                    g[x] = De[x] * t;
+                }
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j)
+                for (int k = 0; k < n; ++k) {
+                    double s = 0.0;
+                    for (int l = 0; l < n; ++l)
+                        for (int m = 0; m < n; ++m)
+                            for (int q = 0; q < n; ++q)
+                                s = s + Sx[i * n + l] * Sy[j * n + m] * Sz[k * n + q]
+                                        * g[((size_t)l * n + m) * n + q];
+                    ve[((size_t)i * n + j) * n + k] = s;
+                }
+    }
+    free(g);
+    return 0;
+}
+
+/* Forward half only (the paper's worked example), lifted form: t = (Sx^T (x) Sy^T (x) Sz^T) u. */
+int tpo_oracle_forward_lifted(const double *u, const double *Sx, const double *Sy,
+                              const double *Sz, double *t, int n, long long num_elems)
+{
+    if (n < 1 || n > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!u || !Sx || !Sy || !Sz || !t) return -1;
+    const size_t cube = (size_t)n * n * n;
+    double *p = (double *)malloc(cube * sizeof(double));
+    double *q = (double *)malloc(cube * sizeof(double));
+    if (!p || !q) { free(p); free(q); return -1; }
+    for (long long e = 0; e < num_elems; ++e) {
+        mode_product(Sz, 1, 2, n, u + (size_t)e * cube, p);
+        mode_product(Sy, 1, 1, n, p, q);
+        mode_product(Sx, 1, 0, n, q, t + (size_t)e * cube);
+    }
+    free(p);
+    free(q);
+    return 0;
+}
+
+int tpo_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

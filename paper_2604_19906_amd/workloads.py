@@ -1,0 +1,179 @@
+"""Seeded synthetic inputs for the batched inverse-Helmholtz tensor-product operator.
+
+This module only *draws inputs*: direction matrices, eigenvalue vectors, per-element shifts,
+fields and the diagonal they define.  It holds none of the operator's arithmetic (no mode
+product, no Kronecker product), so both the CPU oracle's tests and the GPU path's tests may
+import it without sharing any part of the method.
+
+The paper's own workload is a set of spectral elements taken from a Fortran DG-SEM code
+(Sec. 6.1: 8192 elements per run); that data is not public, so the inputs here stand in for
+it with the same structure: many independent elements, one small dense matrix per direction
+shared by all elements, and one strictly positive diagonal cube per element.
+
+Layout: every field is C-contiguous ``[E, n, n, n]`` (element-major, axis 2 fastest); every
+direction matrix is row-major ``[n, n]``.  Axis 0 pairs with ``S_x``/``lam_x``, axis 1 with
+``S_y``/``lam_y`` and axis 2 with ``S_z``/``lam_z``.
+
+Fields are drawn in blocks of ``BLOCK`` elements, block ``b`` from its own seed, so that any
+block of a multi-gigabyte field can be regenerated on its own.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Iterator, Tuple
+
+import numpy as np
+
+BASE_SEED = 19906
+BLOCK = 4096
+
+# stream ids below the (BASE_SEED, config) key
+_STREAM_S, _STREAM_LAM, _STREAM_MU, _STREAM_U = 0, 1, 2, 3
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One synthetic configuration (shape, precision and value distributions)."""
+
+    name: str
+    index: int          # seed key; 0..4 are the five named configurations
+    dtype: str          # "f64" or "f32"
+    n: int              # points per direction (polynomial degree + 1)
+    num_elems: int
+    u_dist: str         # "uniform" -> U(-1,1), "normal" -> N(0,1)
+    distinct_s: bool    # three different direction matrices (and eigenvalue vectors)
+
+    @property
+    def np_dtype(self):
+        return np.float64 if self.dtype == "f64" else np.float32
+
+    @property
+    def word(self) -> int:
+        return 8 if self.dtype == "f64" else 4
+
+    @property
+    def cube(self) -> int:
+        return self.n ** 3
+
+    @property
+    def flop_per_elem(self) -> int:
+        # six mode products of 2 n^4 flop each plus the n^3 diagonal multiplies
+        return 12 * self.n ** 4 + self.n ** 3
+
+    @property
+    def bytes_per_elem(self) -> int:
+        # read u_e, read D_e, write v_e
+        return 3 * self.cube * self.word
+
+
+CONFIGS = (
+    Workload("cfg0_f64_n7_E1000", 0, "f64", 7, 1000, "uniform", False),
+    Workload("cfg1_f64_n8_E131072", 1, "f64", 8, 131072, "uniform", False),
+    Workload("cfg2_f64_n11_E262144", 2, "f64", 11, 262144, "normal", False),
+    Workload("cfg3_f64_n16_E65536", 3, "f64", 16, 65536, "uniform", False),
+    Workload("cfg4_f32_n13_E1048576", 4, "f32", 13, 1048576, "uniform", True),
+)
+
+
+def custom(n: int, num_elems: int, dtype: str = "f64", *, key: int = 100,
+           u_dist: str = "uniform", distinct_s: bool = True) -> Workload:
+    """A workload of arbitrary shape for edge-case tests (``key`` selects the seed)."""
+    return Workload(f"custom_{dtype}_n{n}_E{num_elems}_k{key}", key, dtype, n, num_elems,
+                    u_dist, distinct_s)
+
+
+def _rng(*key: int) -> np.random.Generator:
+    return np.random.default_rng(np.random.SeedSequence([BASE_SEED, *key]))
+
+
+def orthogonal_matrix(n: int, rng: np.random.Generator) -> np.ndarray:
+    """Haar-distributed ``n x n`` orthogonal matrix: Q of a Gaussian's QR with the signs of
+    R's diagonal folded in.  Deterministic for a given generator state; not symmetric."""
+    g = rng.standard_normal((n, n))
+    q, r = np.linalg.qr(g)
+    sgn = np.sign(np.diag(r))
+    sgn[sgn == 0] = 1.0
+    return np.ascontiguousarray(q * sgn[None, :])
+
+
+def direction_matrices(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """``(S_x, S_y, S_z)`` in the workload's dtype.  When the workload shares one matrix the
+    three returned arrays are the same object."""
+    rng = _rng(w.index, _STREAM_S)
+    if w.distinct_s:
+        mats = [orthogonal_matrix(w.n, rng).astype(w.np_dtype) for _ in range(3)]
+        return mats[0], mats[1], mats[2]
+    s = orthogonal_matrix(w.n, rng).astype(w.np_dtype)
+    return s, s, s
+
+
+def eigenvalues(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """``(lam_x, lam_y, lam_z)``, each ``[n]`` fp64 drawn from U(0.1, 10); one vector per
+    direction shared by all elements (the same vector three times if S is shared)."""
+    rng = _rng(w.index, _STREAM_LAM)
+    if w.distinct_s:
+        lams = [rng.uniform(0.1, 10.0, w.n) for _ in range(3)]
+        return lams[0], lams[1], lams[2]
+    lam = rng.uniform(0.1, 10.0, w.n)
+    return lam, lam, lam
+
+
+def shifts(w: Workload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """Per-element shift ``mu_e`` ~ U(0,1), fp64, for elements ``start..stop-1``."""
+    stop = w.num_elems if stop is None else stop
+    out = np.empty(stop - start, dtype=np.float64)
+    for b, lo, hi in _blocks(start, stop):
+        mu_b = _rng(w.index, _STREAM_MU, b).uniform(0.0, 1.0, BLOCK)
+        out[lo - start:hi - start] = mu_b[lo - b * BLOCK:hi - b * BLOCK]
+    return out
+
+
+def _blocks(start: int, stop: int) -> Iterator[Tuple[int, int, int]]:
+    """Yield ``(block id, lo, hi)`` for the parts of ``[start, stop)`` in each seed block."""
+    b = start // BLOCK
+    while b * BLOCK < stop:
+        lo = max(start, b * BLOCK)
+        hi = min(stop, (b + 1) * BLOCK)
+        if hi > lo:
+            yield b, lo, hi
+        b += 1
+
+
+def field_u(w: Workload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """Input field ``u[start:stop]`` of shape ``[stop-start, n, n, n]`` in the workload's
+    dtype.  Values are drawn in fp64 and rounded once."""
+    stop = w.num_elems if stop is None else stop
+    n = w.n
+    out = np.empty((stop - start, n, n, n), dtype=w.np_dtype)
+    for b, lo, hi in _blocks(start, stop):
+        rng = _rng(w.index, _STREAM_U, b)
+        # draw only as many elements of the block as are needed, always from its start
+        cnt = hi - b * BLOCK
+        if w.u_dist == "normal":
+            blk = rng.standard_normal((cnt, n, n, n))
+        else:
+            blk = rng.uniform(-1.0, 1.0, (cnt, n, n, n))
+        out[lo - start:hi - start] = blk[lo - b * BLOCK:]
+    return out
+
+
+def diagonal_d(w: Workload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """Diagonal ``D[e,i,j,k] = 1 / (lam_x[i] + lam_y[j] + lam_z[k] + mu_e)`` for elements
+    ``start..stop-1``, evaluated in fp64 and rounded once to the workload's dtype.  This is
+    the input recipe of the workloads (an input, not a step of the operator)."""
+    stop = w.num_elems if stop is None else stop
+    lx, ly, lz = eigenvalues(w)
+    mu = shifts(w, start, stop)
+    lam3 = lx[:, None, None] + ly[None, :, None] + lz[None, None, :]
+    out = np.empty((stop - start, w.n, w.n, w.n), dtype=w.np_dtype)
+    step = 2048
+    for lo in range(0, stop - start, step):
+        hi = min(stop - start, lo + step)
+        out[lo:hi] = 1.0 / (lam3[None] + mu[lo:hi, None, None, None])
+    return out
+
+
+def make_inputs(w: Workload, start: int = 0, stop: int | None = None):
+    """``(u, S_x, S_y, S_z, D)`` for elements ``start..stop-1`` as host arrays."""
+    sx, sy, sz = direction_matrices(w)
+    return field_u(w, start, stop), sx, sy, sz, diagonal_d(w, start, stop)

@@ -1,0 +1,53 @@
+"""Seeded input generators: determinism, block regeneration, shapes and distributions."""
+import numpy as np
+import pytest
+
+from paper_2604_19906_amd import workloads as wl
+
+
+def test_named_configs():
+    c = wl.CONFIGS
+    assert [(w.dtype, w.n, w.num_elems) for w in c] == [
+        ("f64", 7, 1000), ("f64", 8, 131072), ("f64", 11, 262144),
+        ("f64", 16, 65536), ("f32", 13, 1048576)]
+    assert c[2].u_dist == "normal" and c[4].distinct_s and not c[0].distinct_s
+    assert c[2].flop_per_elem == 12 * 11 ** 4 + 11 ** 3
+    assert c[2].bytes_per_elem == 3 * 1331 * 8
+
+
+def test_deterministic_and_block_regenerable():
+    w = wl.custom(5, 3 * wl.BLOCK + 17, "f64", key=11)
+    a = wl.field_u(w, 4000, 4200)
+    b = wl.field_u(w)[4000:4200]
+    assert np.array_equal(a, b)
+    d1 = wl.diagonal_d(w, wl.BLOCK - 3, wl.BLOCK + 5)
+    d2 = wl.diagonal_d(w)[wl.BLOCK - 3:wl.BLOCK + 5]
+    assert np.array_equal(d1, d2)
+    assert np.array_equal(wl.shifts(w, 10, 20), wl.shifts(w)[10:20])
+    assert wl.field_u(w, 7, 7).shape == (0, 5, 5, 5)
+
+
+def test_direction_matrices_orthogonal_nonsymmetric():
+    for w in (wl.CONFIGS[0], wl.CONFIGS[2], wl.CONFIGS[3]):
+        sx, sy, sz = wl.direction_matrices(w)
+        assert sx is sy and sy is sz
+        assert np.allclose(sx.T @ sx, np.eye(w.n), atol=1e-13)
+        assert not np.allclose(sx, sx.T)
+    w = wl.CONFIGS[4]
+    sx, sy, sz = wl.direction_matrices(w)
+    assert sx.dtype == np.float32 and not np.array_equal(sx, sy) and not np.array_equal(sy, sz)
+    assert np.allclose(sx.astype(np.float64).T @ sx.astype(np.float64), np.eye(13), atol=1e-6)
+
+
+def test_value_ranges():
+    w = wl.CONFIGS[0]
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    assert u.shape == (1000, 7, 7, 7) and u.flags.c_contiguous and d.flags.c_contiguous
+    assert -1 <= u.min() < -0.99 and 0.99 < u.max() <= 1
+    assert d.min() > 1 / 31.0 and d.max() < 1 / 0.3
+    w2 = wl.custom(11, 64, "f64", key=2, u_dist="normal")
+    un = wl.field_u(w2)
+    assert abs(un.mean()) < 0.02 and abs(un.std() - 1) < 0.02
+    w4 = wl.custom(13, 8, "f32", key=4)
+    u4, *_rest, d4 = wl.make_inputs(w4)
+    assert u4.dtype == np.float32 and d4.dtype == np.float32
