@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched inverse-Helmholtz tensor-product operator on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload IDX] [--variant NAME]
+
+A step is one pass of the whole hot path (six mode products plus the diagonal scale, one
+library call) over every element of the workload, with u, D, S and v resident in HBM.  The
+default workload is the fp64 n=11 configuration the headline metric is quoted on.  Prints ONE
+JSON line on stdout; progress goes to stderr.
+
+Beside the whole-job throughput the line carries
+  "roofline":     algorithmic HBM bytes per launch / average kernel time (HIP events on the
+                  launch stream) against the 8 TB/s HBM peak, and the measured HBM traffic per
+                  launch from profiles/traffic.json when it was taken for the current kernel
+                  sources (else null);
+  "cpu_baseline": the CPU oracle, as it stands, timed on this machine's host cores on a
+                  bounded sample of the same workload.  A reported baseline, not a target.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+FP_PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_source_hash() -> str:
+    """Hash of the kernel sources; ties stored HBM-traffic counters to the code they measured."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2604_19906_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".hpp", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(workload: str, variant: str):
+    """HBM bytes per launch from the rocprofv3 --pmc summaries, or None when there is no
+    entry for this workload/variant or the kernel sources changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        table = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    ent = table.get(f"{workload}:{variant}")
+    if not ent or ent.get("source_hash") != kernel_source_hash():
+        return None
+    return ent.get("hbm_bytes_per_launch")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
+    ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma"])
+    ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=131072)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; elements are independent, so a multi-GPU "
+            "run would be a contiguous split of the element range with no exchange. "
+            "Run with --gpus 1.")
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2604_19906_amd import tpo
+    from paper_2604_19906_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 1
+    torch.cuda.set_device(0)
+    tpo.check(tpo.tpo_create(), "tpo_create")      # raises if libtpo.so is missing
+
+    w = wl.CONFIGS[args.workload]
+    if args.elems:
+        w = wl.Workload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems,
+                        w.u_dist, w.distinct_s)
+    variant = {"auto": tpo.TPO_VARIANT_AUTO, "pencil": tpo.TPO_VARIANT_PENCIL,
+               "mfma": tpo.TPO_VARIANT_MFMA}[args.variant]
+    dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
+    chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt)
+    chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma"}[chosen]
+
+    # ---- inputs: seeded, generated block by block on the host, resident in HBM -------------
+    t0 = time.time()
+    tu, tsx, tsy, tsz, td = wl.to_device(w)
+    tv = torch.empty_like(tu)
+    torch.cuda.synchronize()
+    log(f"[bench] {w.name}: inputs resident after {time.time() - t0:.1f}s "
+        f"({3 * tu.numel() * tu.element_size() / 1e9:.2f} GB for u, D, v); variant {chosen_name}")
+
+    stream = torch.cuda.current_stream()
+    ptrs = (tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(), td.data_ptr(),
+            tv.data_ptr())
+
+    def step():
+        rc = tpo.tpo_ihelm_apply_variant(*ptrs, w.n, w.num_elems, dt, stream.cuda_stream, variant)
+        if rc != tpo.TPO_OK:
+            raise tpo.TpoError(rc, "tpo_ihelm_apply")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, device-synchronised on both sides -------------------
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    kernel_ms = [a.elapsed_time(b) for a, b in evs]
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    ms_per_step = wall * 1e3 / args.steps
+
+    elems_per_s = w.num_elems / (ms_per_step * 1e-3)
+    alg_bytes = w.bytes_per_elem * w.num_elems
+    alg_flop = w.flop_per_elem * w.num_elems
+    achieved_gbs = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    achieved_tflops = alg_flop / (avg_kernel_ms * 1e-3) / 1e12
+    log(f"[bench] kernel avg {avg_kernel_ms:.4f} ms (min {min(kernel_ms):.4f}, max "
+        f"{max(kernel_ms):.4f}); wall/step {ms_per_step:.4f} ms; {achieved_gbs:.0f} GB/s; "
+        f"{achieved_tflops:.2f} TFLOP/s")
+
+    # streaming ceiling with the same traffic shape (2 reads + 1 write), library elementwise op
+    for _ in range(3):
+        torch.mul(tu, td, out=tv)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(10):
+        torch.mul(tu, td, out=tv)
+    b.record(stream)
+    torch.cuda.synchronize()
+    stream_ms = a.elapsed_time(b) / 10
+    stream_gbs = alg_bytes / (stream_ms * 1e-3) / 1e9
+    log(f"[bench] streaming ceiling v=u*D: {stream_ms:.4f} ms = {stream_gbs:.0f} GB/s")
+
+    # ---- sanity: the timed output is the operator's (oracle on a few elements) --------------
+    import oracle
+    step()
+    torch.cuda.synchronize()
+    sx, sy, sz = wl.direction_matrices(w)
+    lo, hi = 0, min(64, w.num_elems)
+    ref = oracle.ihelm_apply(wl.field_u(w, lo, hi), sx, sy, sz, wl.diagonal_d(w, lo, hi))
+    err = oracle.max_rel_err_per_element(tv[lo:hi].cpu().numpy(), ref)
+    tol = 1e-12 if w.dtype == "f64" else 2e-5
+    if not err <= tol:
+        log(f"[bench] PARITY FAILURE on the timed output: {err:.3e} > {tol}")
+        return 1
+
+    # ---- CPU baseline: the oracle on this machine's host cores, bounded sample ---------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        ns = min(args.cpu_sample, w.num_elems)
+        hu, hd = wl.field_u(w, 0, ns), wl.diagonal_d(w, 0, ns)
+        cores = oracle.max_threads()
+        oracle.ihelm_apply(hu[:256], sx, sy, sz, hd[:256])          # load + warm
+        t1 = time.perf_counter()
+        oracle.ihelm_apply(hu, sx, sy, sz, hd)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": ns / cpu_s, "unit": "elements/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {ns} elements of {w.name}, one pass, all host threads "
+                         f"({cpu_s:.2f} s wall)",
+               "gflops": ns * w.flop_per_elem / cpu_s / 1e9}
+        log(f"[bench] CPU oracle baseline: {ns / cpu_s:.0f} elements/s on {cores} threads")
+
+    out = {
+        "metric": "elements/s + GFLOP/s and % of binding roofline, fp64 n=11 TPO apply",
+        "value": elems_per_s,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "num_elems": w.num_elems,
+                   "variant": chosen_name, "layout": "[E,n,n,n] element-contiguous",
+                   "parallelism": "1 GPU"},
+        "gflops": alg_flop / (ms_per_step * 1e-3) / 1e9,
+        "kernel_ms_avg": avg_kernel_ms,
+        "kernel_ms_min": min(kernel_ms),
+        "fp_frac_of_peak": achieved_tflops / FP_PEAK_TFLOPS[w.dtype],
+        "stream_ceiling_gbs": stream_gbs,
+        "parity_max_rel_err_sample": err,
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": stored_traffic(w.name, chosen_name)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    tpo.tpo_destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,118 @@
+/*
+ * tpo.h -- C ABI of the MI355X (gfx950) batched inverse-Helmholtz tensor-product operator.
+ *
+ * The operator is the `inv_helm` spectral-element kernel evaluated in the paper (Table 1,
+ * Table 2): per element a forward three-dimensional transform made of one-dimensional mode
+ * products (Sec. 2.2: tensor-product operators are applied "successively as one-dimensional
+ * transformations"; Sec. 5.2 gives the forward triple sum and its lifted, sum-factorised
+ * form), a pointwise scale by a per-element diagonal, and the backward transform:
+ *
+ *   t[i,j,k] = sum_l sum_m sum_q  S_x[l,i] * S_y[m,j] * S_z[q,k] * u_e[l,m,q]
+ *   g[i,j,k] = D_e[i,j,k] * t[i,j,k]
+ *   v_e[i,j,k] = sum_l sum_m sum_q  S_x[i,l] * S_y[j,m] * S_z[k,q] * g[l,m,q]
+ *
+ * i.e. v_e = (S_x (x) S_y (x) S_z) diag(D_e) (S_x (x) S_y (x) S_z)^T u_e on the row-major
+ * flattening of the n*n*n cube.  Elements are independent (Sec. 6.1).
+ *
+ * Plain C types only; no exception crosses this boundary; every function returns a
+ * tpo_status_t (as int) unless stated otherwise.
+ */
+#ifndef TPO_H
+#define TPO_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of u, S_*, D and v.  The arithmetic runs in the same type. */
+typedef enum { TPO_F64 = 0, TPO_F32 = 1 } tpo_dtype_t;
+
+typedef enum {
+    TPO_OK = 0,
+    TPO_ERR_INVALID_ARG = -1,      /* NULL pointer with num_elems > 0, n < 1, num_elems < 0,
+                                      unknown dtype or variant, misaligned pointer */
+    TPO_ERR_UNSUPPORTED = -2,      /* n > TPO_MAX_N, or a variant that has no kernel for (n, dtype) */
+    TPO_ERR_NOT_INITIALIZED = -3,  /* tpo_create has not succeeded on the current device */
+    TPO_ERR_DEVICE = -4,           /* no gfx950 device, or the launch was rejected by HIP */
+    TPO_ERR_ALIAS = -5             /* v overlaps an input other than "v == u exactly" */
+} tpo_status_t;
+
+/* Kernel families (the choice per (n, dtype) is the library's unless forced). */
+typedef enum {
+    TPO_VARIANT_AUTO = 0,    /* the library's measured choice for (n, dtype) */
+    TPO_VARIANT_PENCIL = 1,  /* register-blocked vector FMAs, one pencil per lane */
+    TPO_VARIANT_MFMA = 2     /* matrix-core tiles (v_mfma_f64_16x16x4 / v_mfma_f32_16x16x4) */
+} tpo_variant_t;
+
+#define TPO_MAX_N 16         /* points per direction supported: 1 .. TPO_MAX_N */
+
+/*
+ * tpo_create -- bind the library to the calling thread's current HIP device.
+ * Checks that the device is gfx950 and prepares the kernel table (raises the dynamic
+ * LDS limit of the kernels that need it).  Reference counted per device: every successful
+ * call must be matched by one tpo_destroy.  Allocates no device memory.
+ * Errors: TPO_ERR_DEVICE when there is no usable gfx950 device.
+ */
+int tpo_create(void);
+
+/* tpo_destroy -- drop one reference on the current device.
+ * Errors: TPO_ERR_NOT_INITIALIZED when there is none to drop. */
+int tpo_destroy(void);
+
+/*
+ * tpo_ihelm_apply -- enqueue v_e = (S_x(x)S_y(x)S_z) [ D_e .* ((S_x(x)S_y(x)S_z)^T u_e) ]
+ * for e = 0 .. num_elems-1 (operator above; Sec. 2.2 and Sec. 5.2 of the paper).
+ *
+ *   u, D   DEVICE pointers, read only, [num_elems][n][n][n] C-contiguous (axis 2 fastest)
+ *   v      DEVICE pointer, written, same shape.  v == u (exactly) is allowed: every u_e is
+ *          read on chip before v_e is written.  Any other overlap of v with u, D or an S
+ *          is rejected with TPO_ERR_ALIAS.
+ *   S_x, S_y, S_z
+ *          DEVICE pointers, read only, [n][n] row-major (S[a*n+b]), shared by all elements;
+ *          S_x pairs with cube axis 0 (slowest), S_y with axis 1, S_z with axis 2 (fastest).
+ *          The forward transform applies the transpose of each stored matrix (it sums over
+ *          the first index), the backward transform the matrix itself.  The three pointers
+ *          may be equal.
+ *   n      points per direction (polynomial degree + 1), 1 .. TPO_MAX_N
+ *   num_elems  number of elements E >= 0; 0 is a no-op returning TPO_OK
+ *   dtype  tpo_dtype_t of every array; arithmetic is done in that type
+ *   stream hipStream_t passed as void* (NULL = the default stream)
+ *
+ * Alignment: every pointer must be aligned to its element size (8 or 4 bytes); nothing more
+ * is assumed (odd n makes individual elements only word aligned).
+ * Ownership: the caller owns all buffers before, during and after the call; the library
+ * allocates nothing, keeps no pointer after the kernel has run, and never synchronises: the
+ * call enqueues one kernel on `stream` and returns.  Re-entrant after tpo_create.
+ * Errors (checked on the host, in this order, before any HIP call): TPO_ERR_INVALID_ARG,
+ * TPO_ERR_UNSUPPORTED, TPO_ERR_ALIAS, then TPO_ERR_NOT_INITIALIZED, then TPO_ERR_DEVICE if
+ * HIP rejects the launch.
+ */
+int tpo_ihelm_apply(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                    const void *D, void *v, int n, long long num_elems, int dtype,
+                    void *stream);
+
+/*
+ * tpo_ihelm_apply_variant -- the same operation with the kernel family forced
+ * (tpo_variant_t), for A/B measurements and for testing each family on its own.
+ * TPO_VARIANT_AUTO makes it identical to tpo_ihelm_apply.
+ * Extra error: TPO_ERR_UNSUPPORTED when the family has no kernel for (n, dtype).
+ */
+int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                            const void *D, void *v, int n, long long num_elems, int dtype,
+                            void *stream, int variant);
+
+/* tpo_ihelm_variant_for -- which family TPO_VARIANT_AUTO selects for (n, dtype):
+ * TPO_VARIANT_PENCIL or TPO_VARIANT_MFMA, or TPO_ERR_UNSUPPORTED / TPO_ERR_INVALID_ARG.
+ * Pure host function; needs no device. */
+int tpo_ihelm_variant_for(int n, int dtype);
+
+/* tpo_ihelm_has_variant -- 1 if `variant` has a kernel for (n, dtype), else 0. */
+int tpo_ihelm_has_variant(int n, int dtype, int variant);
+
+/* tpo_status_string -- static, NUL-terminated description of a status; never freed. */
+const char *tpo_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPO_H */

@@ -1,0 +1,145 @@
+// C-ABI entry points of libtpo: per-device reference counting, validation, choice of the
+// kernel family for (n, dtype) and the single kernel launch on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+
+#include "tpo.h"
+#include "tpo_internal.h"
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_mu;
+int g_refs[kMaxDevices] = {0};
+
+// Family chosen by TPO_VARIANT_AUTO, from measurements on MI355X (see profiles/).
+int auto_variant(int n, int dtype)
+{
+    (void)n;
+    (void)dtype;
+    return TPO_VARIANT_PENCIL;
+}
+
+const tpo::KernelEntry *lookup(int n, int dtype, int variant)
+{
+    if (variant == TPO_VARIANT_PENCIL) return tpo::pencil_entry(n, dtype);
+    if (variant == TPO_VARIANT_MFMA) return tpo::mfma_entry(n, dtype);
+    return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tpo_create(void)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TPO_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_refs[dev] == 0) {
+        for (int dt = 0; dt < 2; ++dt)
+            for (int n = 1; n <= TPO_MAX_N; ++n)
+                for (int var : {TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA}) {
+                    const tpo::KernelEntry *k = lookup(n, dt, var);
+                    if (k && k->prepare && k->prepare() != hipSuccess) {
+                        (void)hipGetLastError();
+                        return TPO_ERR_DEVICE;
+                    }
+                }
+    }
+    ++g_refs[dev];
+    return TPO_OK;
+}
+
+int tpo_destroy(void)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_NOT_INITIALIZED;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
+    --g_refs[dev];
+    return TPO_OK;
+}
+
+int tpo_ihelm_variant_for(int n, int dtype)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (n < 1) return TPO_ERR_INVALID_ARG;
+    if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    int var = auto_variant(n, dtype);
+    if (!lookup(n, dtype, var)) var = TPO_VARIANT_PENCIL;
+    return var;
+}
+
+int tpo_ihelm_has_variant(int n, int dtype, int variant)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return 0;
+    if (n < 1 || n > TPO_MAX_N) return 0;
+    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_variant_for(n, dtype);
+    return lookup(n, dtype, variant) != nullptr;
+}
+
+int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                            const void *D, void *v, int n, long long num_elems, int dtype,
+                            void *stream, int variant)
+{
+    const int rc = tpo::validate_apply(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, variant);
+    if (rc != TPO_OK) return rc;
+    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_variant_for(n, dtype);
+    const tpo::KernelEntry *k = lookup(n, dtype, variant);
+    if (!k) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_NOT_INITIALIZED;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
+    }
+    tpo::ApplyArgs a{u, S_x, S_y, S_z, D, v, num_elems, (hipStream_t)stream};
+    if (k->launch(a) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    return TPO_OK;
+}
+
+int tpo_ihelm_apply(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                    const void *D, void *v, int n, long long num_elems, int dtype,
+                    void *stream)
+{
+    return tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, stream,
+                                   TPO_VARIANT_AUTO);
+}
+
+const char *tpo_status_string(int status)
+{
+    switch (status) {
+    case TPO_OK: return "ok";
+    case TPO_ERR_INVALID_ARG: return "invalid argument";
+    case TPO_ERR_UNSUPPORTED: return "unsupported n or kernel variant";
+    case TPO_ERR_NOT_INITIALIZED: return "tpo_create has not been called on this device";
+    case TPO_ERR_DEVICE: return "no gfx950 device or HIP launch failure";
+    case TPO_ERR_ALIAS: return "output overlaps an input (only v == u is allowed)";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

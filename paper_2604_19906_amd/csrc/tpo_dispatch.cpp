@@ -1,0 +1,21 @@
+// Kernel-family lookup: maps (n, dtype) to the instantiation tables of each family.
+#include "tpo_internal.h"
+
+namespace tpo {
+
+const KernelEntry *pencil_entry_f64(int n);
+const KernelEntry *pencil_entry_f32(int n);
+const KernelEntry *mfma_entry_f64(int n);
+const KernelEntry *mfma_entry_f32(int n);
+
+const KernelEntry *pencil_entry(int n, int dtype)
+{
+    return dtype == TPO_F64 ? pencil_entry_f64(n) : pencil_entry_f32(n);
+}
+
+const KernelEntry *mfma_entry(int n, int dtype)
+{
+    return dtype == TPO_F64 ? mfma_entry_f64(n) : mfma_entry_f32(n);
+}
+
+}  // namespace tpo

@@ -1,0 +1,212 @@
+// Register-blocked vector-FMA kernel family ("pencil" kernels) for the batched
+// inverse-Helmholtz tensor-product operator on gfx950.
+//
+// One lane owns one pencil: the n values of the cube along the axis being contracted, for
+// fixed values of the other two indices.  A mode product is then n*n FMAs on registers:
+// the lane's n inputs, n accumulators, and the n*n matrix entries, which are uniform over
+// the wavefront and are read through the scalar data path (s_load + SGPR operand of
+// v_fma), so they cost neither VGPRs nor LDS bandwidth.  Between axes the cube is
+// re-distributed through LDS.  A workgroup processes G whole elements at a time (G*n*n
+// pencils, padded to a multiple of 64 lanes); all six mode products and the diagonal scale
+// run on chip, HBM sees u_e and D_e once (coalesced reads) and v_e once (coalesced store).
+//
+// Order of the six products (mode products along different axes commute):
+//   forward axis 0 (from global, lanes consecutive along (b,c): coalesced)
+//   forward axis 1, forward axis 2, scale by D_e, backward axis 2 (same registers),
+//   backward axis 1, backward axis 0 (to global, coalesced).
+// D_e is loaded coalesced together with u_e and parked in LDS until the scale.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "tpo_internal.h"
+
+namespace tpo {
+
+#define TPO_CONSTANT __attribute__((address_space(4)))
+
+__device__ __forceinline__ double fma_(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float fma_(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
+template <typename T, int N, int G>
+struct PencilShape {
+    static constexpr int P = N * N;                         // pencils per element
+    static constexpr int NT = ((G * P + 63) / 64) * 64;     // threads per workgroup
+    // LDS pitches (in words): row pitch odd, plane pitch odd, so that the three access
+    // patterns (lanes consecutive along c, along c with a in the high part, along b)
+    // spread over the banks.
+    static constexpr int PB = (N & 1) ? N : N + 1;
+    static constexpr int PA = ((N * PB) & 1) ? N * PB : N * PB + 1;
+    static constexpr int CUBE = N * PA;
+    static constexpr size_t LDS_BYTES = (size_t)2 * G * CUBE * sizeof(T);
+};
+
+// Number of elements per workgroup: the G (1..64) with the best lane utilisation among
+// those with at most 512 threads and at most ~53 KB of LDS (three workgroups per CU);
+// G = 1 if nothing fits.
+template <typename T, int N>
+constexpr int pencil_group()
+{
+    int best = 1;
+    long best_num = 0, best_den = 1;  // utilisation = num/den
+    for (int g = 1; g <= 64; ++g) {
+        const int p = g * N * N;
+        const int nt = ((p + 63) / 64) * 64;
+        const int pb = (N & 1) ? N : N + 1;
+        const int pa = ((N * pb) & 1) ? N * pb : N * pb + 1;
+        const long lds = 2L * g * N * pa * (long)sizeof(T);
+        if (nt > 512 || lds > 53 * 1024) break;
+        if ((long)p * best_den > best_num * nt) {
+            best = g;
+            best_num = p;
+            best_den = nt;
+        }
+    }
+    return best;
+}
+
+// y[i] = sum_l S[l][i] * x[l]   (FWD: the transpose of the stored matrix is applied)
+// y[i] = sum_l S[i][l] * x[l]   (!FWD)
+// S is read through the constant address space so that its entries arrive in SGPRs.
+template <typename T, int N, bool FWD>
+__device__ __forceinline__ void mode_product(const TPO_CONSTANT T *S, const T (&x)[N],
+                                             T (&y)[N])
+{
+    // Make the pointer opaque per product: otherwise two products with the same matrix share
+    // one set of scalar loads, all n*n entries stay live across both and spill out of the
+    // SGPR file.
+    asm volatile("" : "+s"(S));
+    if constexpr (FWD) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) y[i] = S[i] * x[0];
+#pragma unroll
+        for (int l = 1; l < N; ++l) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) y[i] = fma_(S[l * N + i], x[l], y[i]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            T acc = S[i * N] * x[0];
+#pragma unroll
+            for (int l = 1; l < N; ++l) acc = fma_(S[i * N + l], x[l], acc);
+            y[i] = acc;
+        }
+    }
+}
+
+template <typename T, int N, int G>
+__global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
+ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
+                    const T *__restrict__ D, T *v, long long num_elems)
+{
+    using Sh = PencilShape<T, N, G>;
+    constexpr int P = Sh::P, PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE;
+    extern __shared__ __align__(16) unsigned char tpo_lds[];
+    T *cube_all = reinterpret_cast<T *>(tpo_lds);
+    T *dpark_all = cube_all + G * CUBE;
+
+    const TPO_CONSTANT T *Sx = (const TPO_CONSTANT T *)Sx_;
+    const TPO_CONSTANT T *Sy = (const TPO_CONSTANT T *)Sy_;
+    const TPO_CONSTANT T *Sz = (const TPO_CONSTANT T *)Sz_;
+
+    const int tid = threadIdx.x;
+    const int g = tid / P;          // element slot inside the workgroup
+    const int p = tid - g * P;      // pencil id inside the element
+    const int hi = p / N;
+    const int lo = p - hi * N;
+    const long long e = (long long)blockIdx.x * G + g;
+    const bool on = (tid < G * P) && (e < num_elems);
+
+    T *cube = cube_all + (g < G ? g : 0) * CUBE;
+    T *dpark = dpark_all + (g < G ? g : 0) * CUBE;
+    const size_t base = (size_t)(on ? e : 0) * (size_t)(N * N * N);
+
+    T x[N], y[N];
+
+    // forward, axis 0: lane (b,c) = (hi,lo); global reads are consecutive over lanes
+    if (on) {
+        T dd[N];
+#pragma unroll
+        for (int l = 0; l < N; ++l) x[l] = u[base + (size_t)(l * P + p)];
+#pragma unroll
+        for (int l = 0; l < N; ++l) dd[l] = D[base + (size_t)(l * P + p)];
+        mode_product<T, N, true>(Sx, x, y);
+#pragma unroll
+        for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
+#pragma unroll
+        for (int l = 0; l < N; ++l) dpark[l * PA + hi * PB + lo] = dd[l];
+    }
+    __syncthreads();
+
+    // forward, axis 1: lane (a,c) = (hi,lo)
+    if (on) {
+#pragma unroll
+        for (int m = 0; m < N; ++m) x[m] = cube[hi * PA + m * PB + lo];
+        mode_product<T, N, true>(Sy, x, y);
+#pragma unroll
+        for (int j = 0; j < N; ++j) cube[hi * PA + j * PB + lo] = y[j];
+    }
+    __syncthreads();
+
+    // forward axis 2, diagonal scale, backward axis 2: lane (a,b) = (hi,lo)
+    if (on) {
+#pragma unroll
+        for (int q = 0; q < N; ++q) x[q] = cube[hi * PA + lo * PB + q];
+        mode_product<T, N, true>(Sz, x, y);
+#pragma unroll
+        for (int k = 0; k < N; ++k) y[k] *= dpark[hi * PA + lo * PB + k];
+        mode_product<T, N, false>(Sz, y, x);
+#pragma unroll
+        for (int k = 0; k < N; ++k) cube[hi * PA + lo * PB + k] = x[k];
+    }
+    __syncthreads();
+
+    // backward, axis 1: lane (a,c) = (hi,lo)
+    if (on) {
+#pragma unroll
+        for (int m = 0; m < N; ++m) x[m] = cube[hi * PA + m * PB + lo];
+        mode_product<T, N, false>(Sy, x, y);
+#pragma unroll
+        for (int j = 0; j < N; ++j) cube[hi * PA + j * PB + lo] = y[j];
+    }
+    __syncthreads();
+
+    // backward, axis 0: lane (b,c) = (hi,lo); global stores are consecutive over lanes
+    if (on) {
+#pragma unroll
+        for (int l = 0; l < N; ++l) x[l] = cube[l * PA + hi * PB + lo];
+        mode_product<T, N, false>(Sx, x, y);
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[base + (size_t)(i * P + p)] = y[i];
+    }
+}
+
+template <typename T, int N>
+struct PencilLauncher {
+    static constexpr int G = pencil_group<T, N>();
+    using Sh = PencilShape<T, N, G>;
+
+    static hipError_t launch(const ApplyArgs &a)
+    {
+        const long long blocks = (a.num_elems + G - 1) / G;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((ihelm_pencil_kernel<T, N, G>), dim3((unsigned)blocks),
+                           dim3(Sh::NT), Sh::LDS_BYTES, a.stream, (const T *)a.u,
+                           (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
+                           (const T *)a.d, (T *)a.v, a.num_elems);
+        return hipGetLastError();
+    }
+
+    static hipError_t prepare()
+    {
+        if (Sh::LDS_BYTES <= 48 * 1024) return hipSuccess;
+        return hipFuncSetAttribute((const void *)ihelm_pencil_kernel<T, N, G>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)Sh::LDS_BYTES);
+    }
+};
+
+#define TPO_PENCIL_ENTRY(T, N) \
+    KernelEntry { &PencilLauncher<T, N>::launch, &PencilLauncher<T, N>::prepare }
+
+}  // namespace tpo

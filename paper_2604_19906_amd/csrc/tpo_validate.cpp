@@ -1,0 +1,45 @@
+// Host-only argument validation for the C ABI (no HIP call is made here, so it runs on a
+// machine without a GPU).
+#include <cstddef>
+#include <cstdint>
+
+#include "tpo.h"
+
+namespace tpo {
+
+static bool overlaps(const void *a, size_t abytes, const void *b, size_t bbytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, a1 = a0 + abytes;
+    const uintptr_t b0 = (uintptr_t)b, b1 = b0 + bbytes;
+    return a0 < b1 && b0 < a1;
+}
+
+int validate_apply(const void *u, const void *sx, const void *sy, const void *sz,
+                   const void *d, const void *v, int n, long long num_elems, int dtype,
+                   int variant)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (variant != TPO_VARIANT_AUTO && variant != TPO_VARIANT_PENCIL &&
+        variant != TPO_VARIANT_MFMA)
+        return TPO_ERR_INVALID_ARG;
+    if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
+    if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+    if (!u || !sx || !sy || !sz || !d || !v) return TPO_ERR_INVALID_ARG;
+    const size_t w = (dtype == TPO_F64) ? 8 : 4;
+    const void *ptrs[6] = {u, sx, sy, sz, d, v};
+    for (const void *p : ptrs)
+        if ((uintptr_t)p % w) return TPO_ERR_INVALID_ARG;
+    // E * n^3 * w must fit in size_t with room to spare (n <= 16, so n^3*w <= 32768)
+    if ((unsigned long long)num_elems > (~(size_t)0 >> 16)) return TPO_ERR_INVALID_ARG;
+    const size_t field = (size_t)num_elems * n * n * n * w;
+    const size_t mat = (size_t)n * n * w;
+    if (v != u && overlaps(v, field, u, field)) return TPO_ERR_ALIAS;
+    if (overlaps(v, field, d, field)) return TPO_ERR_ALIAS;
+    if (overlaps(v, field, sx, mat) || overlaps(v, field, sy, mat) ||
+        overlaps(v, field, sz, mat))
+        return TPO_ERR_ALIAS;
+    return TPO_OK;
+}
+
+}  // namespace tpo

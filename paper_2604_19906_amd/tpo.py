@@ -1,0 +1,120 @@
+"""Thin ctypes binding over libtpo.so: same names as the C ABI in ``include/tpo.h``, argument
+marshalling only.  Every step of the operator runs in the library's HIP kernels; there is no
+fallback: if the library has not been built, loading raises.
+
+Pointers are plain integers (``tensor.data_ptr()``), the stream is a ``hipStream_t`` as an
+integer (``torch.cuda.current_stream().cuda_stream``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+TPO_F64, TPO_F32 = 0, 1
+TPO_OK = 0
+TPO_ERR_INVALID_ARG, TPO_ERR_UNSUPPORTED, TPO_ERR_NOT_INITIALIZED = -1, -2, -3
+TPO_ERR_DEVICE, TPO_ERR_ALIAS = -4, -5
+TPO_VARIANT_AUTO, TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA = 0, 1, 2
+TPO_MAX_N = 16
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtpo.so")
+_lib = None
+
+
+class TpoError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+        self.status = status
+
+
+def lib():
+    """Load libtpo.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2604_19906_amd.build`")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, ci, cll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+        l.tpo_create.argtypes = []
+        l.tpo_create.restype = ci
+        l.tpo_destroy.argtypes = []
+        l.tpo_destroy.restype = ci
+        l.tpo_ihelm_apply.argtypes = [vp, vp, vp, vp, vp, vp, ci, cll, ci, vp]
+        l.tpo_ihelm_apply.restype = ci
+        l.tpo_ihelm_apply_variant.argtypes = [vp, vp, vp, vp, vp, vp, ci, cll, ci, vp, ci]
+        l.tpo_ihelm_apply_variant.restype = ci
+        l.tpo_ihelm_variant_for.argtypes = [ci, ci]
+        l.tpo_ihelm_variant_for.restype = ci
+        l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
+        l.tpo_ihelm_has_variant.restype = ci
+        l.tpo_status_string.argtypes = [ci]
+        l.tpo_status_string.restype = ctypes.c_char_p
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().tpo_status_string(int(status)).decode()
+
+
+def tpo_create() -> int:
+    return lib().tpo_create()
+
+
+def tpo_destroy() -> int:
+    return lib().tpo_destroy()
+
+
+def tpo_ihelm_apply(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, stream) -> int:
+    """Raw call: integer device pointers in, status out."""
+    return lib().tpo_ihelm_apply(u, S_x, S_y, S_z, D, v, int(n), int(num_elems), int(dtype),
+                                 stream)
+
+
+def tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, stream,
+                            variant) -> int:
+    return lib().tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, int(n), int(num_elems),
+                                         int(dtype), stream, int(variant))
+
+
+def tpo_ihelm_variant_for(n: int, dtype: int) -> int:
+    return lib().tpo_ihelm_variant_for(int(n), int(dtype))
+
+
+def tpo_ihelm_has_variant(n: int, dtype: int, variant: int) -> bool:
+    return bool(lib().tpo_ihelm_has_variant(int(n), int(dtype), int(variant)))
+
+
+def check(status: int, what: str = "tpo call") -> None:
+    if status != TPO_OK:
+        raise TpoError(status, what)
+
+
+def apply_tensors(u, S_x, S_y, S_z, D, v=None, variant: int = TPO_VARIANT_AUTO):
+    """Convenience over torch device tensors: marshals pointers, shape and the current
+    stream; raises TpoError on a non-zero status.  Returns ``v`` (allocated if None)."""
+    import torch
+
+    if u.dim() != 4 or not u.is_cuda:
+        raise ValueError("u must be a device tensor of shape [E,n,n,n]")
+    for t in (u, S_x, S_y, S_z, D):
+        if not t.is_contiguous() or t.dtype != u.dtype or not t.is_cuda:
+            raise ValueError("all tensors must be contiguous device tensors of one dtype")
+    e, n = u.shape[0], u.shape[1]
+    if tuple(u.shape[1:]) != (n, n, n) or tuple(D.shape) != tuple(u.shape):
+        raise ValueError("u and D must both be [E,n,n,n]")
+    for s in (S_x, S_y, S_z):
+        if tuple(s.shape) != (n, n):
+            raise ValueError("S matrices must be [n,n]")
+    if v is None:
+        v = torch.empty_like(u)
+    elif (tuple(v.shape) != tuple(u.shape) or v.dtype != u.dtype or not v.is_contiguous()
+          or not v.is_cuda):
+        raise ValueError("v must match u")
+    dtype = {torch.float64: TPO_F64, torch.float32: TPO_F32}[u.dtype]
+    stream = torch.cuda.current_stream().cuda_stream
+    check(tpo_ihelm_apply_variant(u.data_ptr(), S_x.data_ptr(), S_y.data_ptr(),
+                                  S_z.data_ptr(), D.data_ptr(), v.data_ptr(), n, e, dtype,
+                                  stream, variant), "tpo_ihelm_apply")
+    return v

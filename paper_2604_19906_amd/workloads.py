@@ -177,3 +177,34 @@ def make_inputs(w: Workload, start: int = 0, stop: int | None = None):
     """``(u, S_x, S_y, S_z, D)`` for elements ``start..stop-1`` as host arrays."""
     sx, sy, sz = direction_matrices(w)
     return field_u(w, start, stop), sx, sy, sz, diagonal_d(w, start, stop)
+
+
+def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK):
+    """Device tensors ``(u, S_x, S_y, S_z, D)`` of a whole workload on the current GPU.
+    Fields are generated block by block on the host (each block from its own seed, several
+    blocks at a time) and copied into place, so host memory stays small even for fields of
+    many gigabytes.  A shared matrix is uploaded once and returned three times."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import torch
+
+    e, n = w.num_elems, w.n
+    tdtype = torch.float64 if w.dtype == "f64" else torch.float32
+    tu = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")
+    td = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")
+    spans = [(lo, min(e, lo + chunk)) for lo in range(0, e, chunk)]
+
+    def gen(span):
+        lo, hi = span
+        return lo, hi, field_u(w, lo, hi), diagonal_d(w, lo, hi)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for lo, hi, hu, hd in ex.map(gen, spans):
+            tu[lo:hi].copy_(torch.from_numpy(hu))
+            td[lo:hi].copy_(torch.from_numpy(hd))
+    sx, sy, sz = direction_matrices(w)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    if sx is sy and sy is sz:
+        ts = up(sx)
+        return tu, ts, ts, ts, td
+    return tu, up(sx), up(sy), up(sz), td

@@ -1,0 +1,102 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and validates arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_19906_amd import tpo
+
+
+def declared_functions(repo_root):
+    text = open(os.path.join(repo_root, "include", "tpo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tpo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    names = declared_functions(repo_root)
+    assert {"tpo_create", "tpo_destroy", "tpo_ihelm_apply", "tpo_status_string"} <= set(names)
+    l = tpo.lib()
+    for name in names:
+        assert hasattr(l, name), f"{name} declared in tpo.h but not exported"
+
+
+def test_status_strings():
+    for s in (0, -1, -2, -3, -4, -5):
+        assert len(tpo.status_string(s)) > 1
+    assert tpo.status_string(0) == "ok"
+    assert "unknown" in tpo.status_string(-99)
+
+
+def _buf(nbytes):
+    a = np.zeros(nbytes // 8 + 2, dtype=np.float64)
+    return a, a.ctypes.data
+
+
+def test_argument_validation_precedes_any_device_use():
+    # Host addresses stand in for device pointers: validation only looks at their values.
+    n, e = 4, 10
+    keep, p = [], []
+    for _ in range(6):
+        a, addr = _buf(e * n ** 3 * 8)
+        keep.append(a)
+        p.append(addr)
+    u, sx, sy, sz, d, v = p
+    ap = tpo.tpo_ihelm_apply
+    assert ap(u, sx, sy, sz, d, v, 0, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, -3, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, n, -1, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, n, e, 7, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, 17, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    assert ap(u, sx, sy, sz, d, v, 1000, e, tpo.TPO_F32, None) == tpo.TPO_ERR_UNSUPPORTED
+    for k in range(6):
+        q = list(p)
+        q[k] = None
+        assert ap(*q, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    # misaligned pointer
+    assert ap(u + 4, sx, sy, sz, d, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u + 2, sx, sy, sz, d, v, n, e, tpo.TPO_F32, None) == tpo.TPO_ERR_INVALID_ARG
+    # aliasing: partial overlap with u, any overlap with D or S
+    assert ap(u, sx, sy, sz, d, u + 8, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, d, d, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, d, d + 64, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, v + 16, sy, sz, d, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, v, d, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    # unknown variant
+    assert tpo.tpo_ihelm_apply_variant(u, sx, sy, sz, d, v, n, e, tpo.TPO_F64, None, 9) \
+        == tpo.TPO_ERR_INVALID_ARG
+    # empty batch is a no-op, even with NULL data pointers
+    assert ap(None, None, None, None, None, None, n, 0, tpo.TPO_F64, None) == tpo.TPO_OK
+
+
+def test_valid_call_without_create_reports_not_initialized():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("covered by the GPU tests")
+    n, e = 3, 2
+    keep, p = [], []
+    for _ in range(6):
+        a, addr = _buf(e * n ** 3 * 8)
+        keep.append(a)
+        p.append(addr)
+    # in-place (v == u) passes the alias check; without a device nothing is launched
+    rc = tpo.tpo_ihelm_apply(p[0], p[1], p[2], p[3], p[4], p[0], n, e, tpo.TPO_F64, None)
+    assert rc == tpo.TPO_ERR_NOT_INITIALIZED
+    assert tpo.tpo_destroy() == tpo.TPO_ERR_NOT_INITIALIZED
+    assert tpo.tpo_create() == tpo.TPO_ERR_DEVICE
+
+
+def test_variant_queries():
+    for dt in (tpo.TPO_F64, tpo.TPO_F32):
+        for n in range(1, tpo.TPO_MAX_N + 1):
+            var = tpo.tpo_ihelm_variant_for(n, dt)
+            assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA)
+            assert tpo.tpo_ihelm_has_variant(n, dt, var)
+            assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
+    assert tpo.tpo_ihelm_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
+    assert tpo.tpo_ihelm_variant_for(0, tpo.TPO_F64) == tpo.TPO_ERR_INVALID_ARG
+    assert tpo.tpo_ihelm_variant_for(4, 5) == tpo.TPO_ERR_INVALID_ARG
+    assert not tpo.tpo_ihelm_has_variant(17, tpo.TPO_F64, tpo.TPO_VARIANT_PENCIL)

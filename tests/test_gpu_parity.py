@@ -1,0 +1,214 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bar: max-norm relative error per element <= 1e-12 (fp64) / 2e-5 (fp32)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, VARIANTS, dev, run, upload_full
+from paper_2604_19906_amd import tpo
+from paper_2604_19906_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f64": tpo.TPO_F64, "f32": tpo.TPO_F32}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def library():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    tpo.check(tpo.tpo_create(), "tpo_create")
+    yield
+    tpo.check(tpo.tpo_destroy(), "tpo_destroy")
+
+
+def variants_for(n, dtype):
+    return [name for name, var in VARIANTS.items() if tpo.tpo_ihelm_has_variant(n, DT[dtype], var)]
+
+
+def check_against_oracle(w, variant_name, lo=0, hi=None):
+    u, sx, sy, sz, d = wl.make_inputs(w, lo, hi)
+    got = run(u, sx, sy, sz, d, VARIANTS[variant_name])
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    assert got.dtype == u.dtype and got.shape == u.shape
+    err = oracle.max_rel_err_per_element(got, ref)
+    assert err <= TOL[w.dtype], f"{w.name} {variant_name}: err {err:.3e}"
+    return err
+
+
+# every supported n, both precisions, every kernel family; E spans several workgroups and
+# leaves a ragged tail for every group size
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", list(range(1, 17)))
+def test_all_n_small_batches(n, dtype):
+    for name in variants_for(n, dtype):
+        for e in (1, 67, 203):
+            w = wl.custom(n, e, dtype, key=200 + n, distinct_s=True)
+            print(f"case n={n} {dtype} E={e} variant={name}", flush=True)
+            check_against_oracle(w, name)
+
+
+def test_config0_all_elements():
+    w = wl.CONFIGS[0]
+    for name in variants_for(w.n, w.dtype):
+        check_against_oracle(w, name)
+    # the default entry point (10 arguments) picks its own family
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    tu, ts, td = dev(u), dev(sx), dev(d)
+    tv = torch.empty_like(tu)
+    rc = tpo.tpo_ihelm_apply(tu.data_ptr(), ts.data_ptr(), ts.data_ptr(), ts.data_ptr(),
+                             td.data_ptr(), tv.data_ptr(), w.n, w.num_elems, tpo.TPO_F64,
+                             torch.cuda.current_stream().cuda_stream)
+    assert rc == tpo.TPO_OK
+    torch.cuda.synchronize()
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    assert oracle.max_rel_err_per_element(tv.cpu().numpy(), ref) <= 1e-12
+
+
+def test_golden_file(repo_root):
+    path = os.path.join(repo_root, "tests", "golden", "ihelm_f64_n3_E2.txt")
+    want = np.array([float.fromhex(l) for l in open(path) if not l.startswith("#")])
+    w = wl.custom(3, 2, "f64", key=77)
+    for name in variants_for(3, "f64"):
+        got = run(*wl.make_inputs(w), VARIANTS[name])
+        assert oracle.max_rel_err_per_element(got, want.reshape(got.shape)) <= 1e-12
+
+
+def sample_spans(e):
+    """First and last 512 elements plus eight seeded 256-element windows."""
+    rng = np.random.default_rng(12345 + e)
+    spans = [(0, min(512, e)), (max(0, e - 512), e)]
+    for s in rng.integers(0, max(1, e - 256), 8):
+        spans.append((int(s), int(min(e, s + 256))))
+    return spans
+
+
+def torch_reference_chunk(u, sx, sy, sz, d):
+    """Independent full-coverage cross-check (library einsum on the device; not the oracle)."""
+    t = torch.einsum("li,mj,qk,elmq->eijk", sx, sy, sz, u)
+    return torch.einsum("il,jm,kq,elmq->eijk", sx, sy, sz, d * t)
+
+
+# the four large configurations at full size, in the launch configuration the benchmark uses
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_full_size_configs(idx):
+    w = wl.CONFIGS[idx]
+    print(f"case {w.name}: generating", flush=True)
+    tu, tsx, tsy, tsz, td = upload_full(w)
+    tv = torch.empty_like(tu)
+    for name in variants_for(w.n, w.dtype):
+        print(f"case {w.name} variant={name}", flush=True)
+        tv.fill_(float("nan"))
+        tpo.apply_tensors(tu, tsx, tsy, tsz, td, tv, variant=VARIANTS[name])
+        torch.cuda.synchronize()
+        # (1) oracle on sampled windows, element by element
+        sx, sy, sz = wl.direction_matrices(w)
+        worst = 0.0
+        for lo, hi in sample_spans(w.num_elems):
+            u = wl.field_u(w, lo, hi)
+            d = wl.diagonal_d(w, lo, hi)
+            assert np.array_equal(u, tu[lo:hi].cpu().numpy())      # same inputs on both sides
+            ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+            err = oracle.max_rel_err_per_element(tv[lo:hi].cpu().numpy(), ref)
+            worst = max(worst, err)
+        assert worst <= TOL[w.dtype], f"{w.name} {name}: sampled err {worst:.3e}"
+        # (2) every element: no NaN left, and agreement with a device einsum in fp64
+        assert not torch.isnan(tv).any()
+        step = 8192
+        worst_all = 0.0
+        s64 = [s.double() for s in (tsx, tsy, tsz)]
+        for lo in range(0, w.num_elems, step):
+            hi = min(w.num_elems, lo + step)
+            ref = torch_reference_chunk(tu[lo:hi].double(), *s64, td[lo:hi].double())
+            num = (tv[lo:hi].double() - ref).abs().flatten(1).max(dim=1).values
+            den = ref.abs().flatten(1).max(dim=1).values
+            worst_all = max(worst_all, float((num / den).max()))
+        assert worst_all <= TOL[w.dtype], f"{w.name} {name}: full err {worst_all:.3e}"
+        print(f"  {w.name} {name}: sampled {worst:.2e}, all elements {worst_all:.2e}", flush=True)
+
+
+def test_in_place_and_determinism():
+    for dtype, n, e in (("f64", 11, 301), ("f32", 13, 150), ("f64", 16, 40), ("f64", 8, 77)):
+        w = wl.custom(n, e, dtype, key=300 + n)
+        u, sx, sy, sz, d = wl.make_inputs(w)
+        for name in variants_for(n, dtype):
+            var = VARIANTS[name]
+            tu, tsx, tsy, tsz, td = map(dev, (u, sx, sy, sz, d))
+            v1 = tpo.apply_tensors(tu, tsx, tsy, tsz, td, variant=var)
+            v2 = tpo.apply_tensors(tu, tsx, tsy, tsz, td, variant=var)
+            assert torch.equal(v1, v2)                       # bitwise repeatable
+            tpo.apply_tensors(tu, tsx, tsy, tsz, td, tu, variant=var)   # v == u
+            assert torch.equal(tu, v1)
+
+
+def test_equal_valued_matrices_in_distinct_buffers():
+    w = wl.custom(7, 90, "f64", key=41, distinct_s=False)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    for name in variants_for(7, "f64"):
+        a = run(u, sx, sy, sz, d, VARIANTS[name], same_s_pointer=True)
+        b = run(u, sx, sy.copy(), sz.copy(), d, VARIANTS[name], same_s_pointer=False)
+        assert np.array_equal(a, b)
+
+
+def test_word_aligned_base_pointers():
+    # fields that start one word into an allocation: only 8-byte (4-byte) aligned
+    for dtype, n, e in (("f64", 11, 64), ("f32", 13, 64), ("f32", 5, 33)):
+        w = wl.custom(n, e, dtype, key=500 + n)
+        u, sx, sy, sz, d = wl.make_inputs(w)
+        ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+        for name in variants_for(n, dtype):
+            def shifted(a):
+                flat = torch.empty(a.size + 1, dtype=dev(a).dtype, device="cuda")
+                view = flat[1:].view(a.shape)
+                view.copy_(torch.from_numpy(a))
+                return view
+            tu, td = shifted(u), shifted(d)
+            tsx, tsy, tsz = shifted(sx), shifted(sy), shifted(sz)
+            tv = shifted(np.zeros_like(u))
+            tpo.apply_tensors(tu, tsx, tsy, tsz, td, tv, variant=VARIANTS[name])
+            torch.cuda.synchronize()
+            assert oracle.max_rel_err_per_element(tv.cpu().numpy(), ref) <= TOL[dtype]
+
+
+def test_side_stream_ordering():
+    w = wl.custom(9, 500, "f64", key=61)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    s = torch.cuda.Stream()
+    tsx, tsy, tsz, td = map(dev, (sx, sy, sz, d))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        tu = torch.from_numpy(u).cuda()          # upload, apply and scale on the same stream
+        tv = tpo.apply_tensors(tu, tsx, tsy, tsz, td)
+        tv2 = tv * 2.0
+    s.synchronize()
+    assert oracle.max_rel_err_per_element(tv2.cpu().numpy(), 2.0 * ref) <= 1e-12
+
+
+def test_status_codes_on_device():
+    w = wl.custom(4, 8, "f64", key=71)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    tu, tsx, tsy, tsz, td = map(dev, (u, sx, sy, sz, d))
+    tv = torch.empty_like(tu)
+    st = torch.cuda.current_stream().cuda_stream
+    args = (tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(), td.data_ptr(),
+            tv.data_ptr())
+    assert tpo.tpo_ihelm_apply(*args, 4, 0, tpo.TPO_F64, st) == tpo.TPO_OK       # empty batch
+    assert tpo.tpo_ihelm_apply(*args, 17, 8, tpo.TPO_F64, st) == tpo.TPO_ERR_UNSUPPORTED
+    assert tpo.tpo_ihelm_apply(*args[:5], td.data_ptr(), 4, 8, tpo.TPO_F64, st) \
+        == tpo.TPO_ERR_ALIAS
+    # reference counting: a second create/destroy pair leaves the library usable
+    assert tpo.tpo_create() == tpo.TPO_OK
+    assert tpo.tpo_destroy() == tpo.TPO_OK
+    assert tpo.tpo_ihelm_apply(*args, 4, 8, tpo.TPO_F64, st) == tpo.TPO_OK
+    # dropping the last reference makes apply refuse; creating again restores it
+    assert tpo.tpo_destroy() == tpo.TPO_OK
+    assert tpo.tpo_ihelm_apply(*args, 4, 8, tpo.TPO_F64, st) == tpo.TPO_ERR_NOT_INITIALIZED
+    assert tpo.tpo_destroy() == tpo.TPO_ERR_NOT_INITIALIZED
+    assert tpo.tpo_create() == tpo.TPO_OK
+    assert tpo.tpo_ihelm_apply(*args, 4, 8, tpo.TPO_F64, st) == tpo.TPO_OK
+    torch.cuda.synchronize()
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    assert oracle.max_rel_err_per_element(tv.cpu().numpy(), ref) <= 1e-12
