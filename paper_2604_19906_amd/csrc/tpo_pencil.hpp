@@ -94,7 +94,22 @@ __device__ __forceinline__ void mode_product(const TPO_CONSTANT T *S, const T (&
     }
 }
 
-template <typename T, int N, int G>
+// Global accesses with or without the non-temporal hint (streamed once, never re-read).
+template <bool NT, typename T>
+__device__ __forceinline__ T gload(const T *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void gstore(T *p, T x)
+{
+    if constexpr (NT) __builtin_nontemporal_store(x, p);
+    else *p = x;
+}
+
+// HINT bit 0: non-temporal loads of u and D; bit 1: non-temporal stores of v.
+template <typename T, int N, int G, int HINT>
 __global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
 ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
                     const T *__restrict__ D, T *v, long long num_elems)
@@ -127,9 +142,9 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     if (on) {
         T dd[N];
 #pragma unroll
-        for (int l = 0; l < N; ++l) x[l] = u[base + (size_t)(l * P + p)];
+        for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base + (size_t)(l * P + p));
 #pragma unroll
-        for (int l = 0; l < N; ++l) dd[l] = D[base + (size_t)(l * P + p)];
+        for (int l = 0; l < N; ++l) dd[l] = gload<(HINT & 1) != 0>(D + base + (size_t)(l * P + p));
         mode_product<T, N, true>(Sx, x, y);
 #pragma unroll
         for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
@@ -177,20 +192,34 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
         for (int l = 0; l < N; ++l) x[l] = cube[l * PA + hi * PB + lo];
         mode_product<T, N, false>(Sx, x, y);
 #pragma unroll
-        for (int i = 0; i < N; ++i) v[base + (size_t)(i * P + p)] = y[i];
+        for (int i = 0; i < N; ++i) gstore<(HINT & 2) != 0>(v + base + (size_t)(i * P + p), y[i]);
     }
 }
 
+// Elements per workgroup and hint bits per (type, n).  The defaults are the lane-utilisation
+// rule and non-temporal stores; the specialisations are the best of a sweep on MI355X over
+// G in {1,2,4,8} and the four hint combinations at the sizes of the named workloads.
+template <typename T, int N>
+struct PencilTune {
+    static constexpr int G = pencil_group<T, N>();
+    static constexpr int HINT = 2;
+};
+template <> struct PencilTune<double, 8> { static constexpr int G = 4, HINT = 3; };
+template <> struct PencilTune<double, 11> { static constexpr int G = 1, HINT = 2; };
+template <> struct PencilTune<double, 16> { static constexpr int G = 1, HINT = 3; };
+template <> struct PencilTune<float, 13> { static constexpr int G = 3, HINT = 0; };
+
 template <typename T, int N>
 struct PencilLauncher {
-    static constexpr int G = pencil_group<T, N>();
+    static constexpr int G = PencilTune<T, N>::G;
+    static constexpr int HINT = PencilTune<T, N>::HINT;
     using Sh = PencilShape<T, N, G>;
 
     static hipError_t launch(const ApplyArgs &a)
     {
         const long long blocks = (a.num_elems + G - 1) / G;
         if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((ihelm_pencil_kernel<T, N, G>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((ihelm_pencil_kernel<T, N, G, HINT>), dim3((unsigned)blocks),
                            dim3(Sh::NT), Sh::LDS_BYTES, a.stream, (const T *)a.u,
                            (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
@@ -200,7 +229,7 @@ struct PencilLauncher {
     static hipError_t prepare()
     {
         if (Sh::LDS_BYTES <= 48 * 1024) return hipSuccess;
-        return hipFuncSetAttribute((const void *)ihelm_pencil_kernel<T, N, G>,
+        return hipFuncSetAttribute((const void *)ihelm_pencil_kernel<T, N, G, HINT>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)Sh::LDS_BYTES);
     }
