@@ -109,6 +109,17 @@ int tpo_ihelm_variant_for(int n, int dtype);
 /* tpo_ihelm_has_variant -- 1 if `variant` has a kernel for (n, dtype), else 0. */
 int tpo_ihelm_has_variant(int n, int dtype, int variant);
 
+/*
+ * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming
+ * kernel v[i] = u[i] * D[i], i < count, over flat DEVICE arrays of `dtype`.  It moves the
+ * operator's algorithmic traffic (two reads and one write per word) and nothing else, so the
+ * benchmark uses its time as the streaming ceiling and its HBM counters to calibrate those
+ * of the operator's kernels.  Pointers must be 16-byte aligned; no aliasing check is made
+ * (v == u is fine).  Needs no tpo_create.  Errors: TPO_ERR_INVALID_ARG, TPO_ERR_DEVICE.
+ */
+int tpo_stream_scale(const void *u, const void *D, void *v, long long count, int dtype,
+                     void *stream);
+
 /* tpo_status_string -- static, NUL-terminated description of a status; never freed. */
 const char *tpo_status_string(int status);
 

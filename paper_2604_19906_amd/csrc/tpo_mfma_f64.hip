@@ -1,0 +1,33 @@
+// Instantiations of the matrix-core kernel family for double, n = 1 .. 16.
+#include "tpo_mfma.hpp"
+
+namespace tpo {
+
+// Elements per workgroup, wavefronts per workgroup and hint bits per n.  The default deals
+// at least eight tiles to four wavefronts; the specialisations come from a sweep on MI355X.
+template <int N>
+struct MfmaTune_f64 {
+    static constexpr int TILES = (N * N + 15) / 16;
+    static constexpr int G = (8 + TILES - 1) / TILES;
+    static constexpr int NW = 4;
+    static constexpr int HINT = 2;
+};
+
+#define ENTRY(N)                                                                          \
+    KernelEntry {                                                                         \
+        &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
+                      MfmaTune_f64<N>::HINT>::launch,                                   \
+        &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
+                      MfmaTune_f64<N>::HINT>::prepare                                   \
+    }
+
+const KernelEntry *mfma_entry_f64(int n)
+{
+    static const KernelEntry table[TPO_MAX_N] = {
+        ENTRY(1),  ENTRY(2),  ENTRY(3),  ENTRY(4),  ENTRY(5),  ENTRY(6),  ENTRY(7),  ENTRY(8),
+        ENTRY(9),  ENTRY(10), ENTRY(11), ENTRY(12), ENTRY(13), ENTRY(14), ENTRY(15), ENTRY(16),
+    };
+    return (n >= 1 && n <= TPO_MAX_N) ? &table[n - 1] : nullptr;
+}
+
+}  // namespace tpo

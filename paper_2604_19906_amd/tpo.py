@@ -48,6 +48,8 @@ def lib():
         l.tpo_ihelm_variant_for.restype = ci
         l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_has_variant.restype = ci
+        l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
+        l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
         l.tpo_status_string.restype = ctypes.c_char_p
         _lib = l
@@ -84,6 +86,11 @@ def tpo_ihelm_variant_for(n: int, dtype: int) -> int:
 
 def tpo_ihelm_has_variant(n: int, dtype: int, variant: int) -> bool:
     return bool(lib().tpo_ihelm_has_variant(int(n), int(dtype), int(variant)))
+
+
+def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:
+    """Measurement aid: v[i] = u[i] * D[i] over flat device arrays (streaming ceiling)."""
+    return lib().tpo_stream_scale(u, D, v, int(count), int(dtype), stream)
 
 
 def check(status: int, what: str = "tpo call") -> None:
