@@ -64,8 +64,8 @@ def stored_traffic(workload: str, variant: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
     ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma"])
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")

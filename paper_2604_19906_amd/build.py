@@ -24,6 +24,8 @@ ARCH = "gfx950"
 HIP_FLAGS = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
              "-Wno-unused-parameter",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # keep MFMA accumulators in ordinary VGPRs (no AGPR copies around every tile)
+             "-mllvm", "-amdgpu-mfma-vgpr-form",
              "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

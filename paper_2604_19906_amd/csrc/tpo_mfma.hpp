@@ -4,33 +4,43 @@
 // A mode product along one axis of the cube is the matrix product
 //     Out[i, X] = sum_l Mat[i, l] * In[l, X],      X = the other two indices, flattened,
 // with Mat = S^T (forward) or S (backward).  It is cut into 16-column tiles of X; one tile
-// is  D(16x16) = sum over k-steps of  A(16x4) * B(4x16)  with
-//     A = Mat[:, 4 values of l]   (the same for every tile: held in registers for the whole
-//                                  kernel, zero beyond n),
-//     B = In[4 values of l, 16 columns]   (one word per lane per k-step, read from LDS).
-// The accumulator leaves lane (x, g) holding Out[row(r,g), X0+x], r = 0..3, with
-// row(r,g) = 4r+g for f64 and 4g+r for f32.  A tile overwrites its own columns in LDS, so a
-// mode product needs no second buffer, and nothing between the first load of u_e and the
-// store of v_e touches HBM.
+// is  D(16x16) = sum over KS = ceil(n/4) k-steps of  A(16x4) * B(4x16)  with
+//     A = Mat rows x 4 values of l   (the same for every tile: held in registers for the
+//                                     whole kernel, zero beyond n),
+//     B = In[4 values of l, 16 columns]   (one word per lane per k-step).
+// Lane (x, g) of a wavefront (x = lane % 16, g = lane / 16) supplies column x of B and gets
+// column x of the result.  The numbering of l over (k-step s, lane group g) and of the
+// result rows over (accumulator register r, lane group g) is free, because the rows and
+// k-columns of A can be permuted to match; both are chosen as
+//     l = off(g) + s,      i = off(g) + r   (r < KS),      off(g) = min(g*KS, n-KS),
+// so that a lane always holds KS CONSECUTIVE indices of the contracted axis, all inside the
+// cube (the last lane groups slide back and overlap; the overlap is zeroed in A's k-columns).
+// Consequences:
+//   * along the fastest axis the lane's words are contiguous in memory, so the first product
+//     reads u_e and the last product writes v_e straight from/to HBM with every wavefront
+//     instruction covering one contiguous run of 16 rows of the [n*n, n] matrix;
+//   * the accumulators of a forward product are, unchanged, the B operands of the backward
+//     product along the same axis: the diagonal scale and the turn-around need no LDS.
 //
-// Order: forward axis 0 (B read straight from HBM: lanes run along X, so rows of 16 words
-// are contiguous), forward axis 1, forward axis 2, scale by D_e, backward axis 2, backward
-// axis 1, backward axis 0 (accumulators stored straight to HBM).  After forward axis 2 the
-// accumulator rows are exactly the l-values a k-step needs when the contraction index is
-// numbered row(s,g), so the scaled accumulators are fed back as B operands of backward
-// axis 2 without leaving registers.  D_e is copied to LDS (coalesced) while forward axis 0
-// runs and is read from there in accumulator layout.
+// Order: forward axis 2 (B from HBM), forward axis 1, forward axis 0, scale by D_e (loaded
+// from HBM in accumulator layout at kernel start), backward axis 0 (registers), backward
+// axis 1, backward axis 2 (accumulators to HBM).  Between products the cube lives in LDS, one
+// buffer, updated in place: a tile reads and writes only its own columns.  Nothing between
+// the load of u_e, D_e and the store of v_e touches HBM.
 //
-// A workgroup of NW wavefronts handles G elements; the G*ceil(n*n/16) tiles of a mode
-// product are dealt round-robin to the wavefronts, with a barrier between mode products.
+// A workgroup of NW wavefronts handles G elements; the G*ceil(n*n/16) tiles of a product are
+// dealt round-robin to the wavefronts, with a barrier between products.
 #pragma once
 #include <hip/hip_runtime.h>
 
 #include "tpo_internal.h"
-#include "tpo_pencil.hpp"   // PencilShape pitches, gload/gstore, lds_index
+#include "tpo_pencil.hpp"   // PencilShape pitches, gload/gstore
 
 namespace tpo {
 
+// Hardware layouts (checked on gfx950): A[m][k] is read from lane 16*k + m, B[k][n] from lane
+// 16*k + n, and accumulator register r of lane (x, g) is D[m][x] with m = 4r+g (f64) or
+// m = 4g+r (f32).  split() undoes that: hardware row m -> (lane group, register).
 template <typename T> struct Mfma;
 template <> struct Mfma<double> {
     typedef double acc_t __attribute__((ext_vector_type(4)));
@@ -38,7 +48,7 @@ template <> struct Mfma<double> {
     {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int row(int r, int g) { return 4 * r + g; }
+    static __device__ __forceinline__ void split(int m, int &grp, int &reg) { grp = m & 3; reg = m >> 2; }
 };
 template <> struct Mfma<float> {
     typedef float acc_t __attribute__((ext_vector_type(4)));
@@ -46,7 +56,7 @@ template <> struct Mfma<float> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int row(int r, int g) { return 4 * g + r; }
+    static __device__ __forceinline__ void split(int m, int &grp, int &reg) { grp = m >> 2; reg = m & 3; }
 };
 
 template <typename T, int N, int G, int NW>
@@ -57,13 +67,60 @@ struct MfmaShape {
     static constexpr int TILES = (P2 + 15) / 16;            // column tiles per element
     static constexpr int TT = G * TILES;                    // tiles per workgroup
     static constexpr int TPW = (TT + NW - 1) / NW;          // tiles per wavefront
-    static constexpr int KS = (N + 3) / 4;                  // k-steps, l = 4s+g
-    // k-steps of the register-fed backward product, l = row(s,g)
-    static constexpr int KSF = (sizeof(T) == 8) ? KS : (N < 4 ? N : 4);
+    static constexpr int KS = (N + 3) / 4;                  // k-steps; words per lane
     static constexpr int NT = 64 * NW;
     static constexpr int PA = Pitch::PA, PB = Pitch::PB, CUBE = Pitch::CUBE;
-    static constexpr size_t LDS_BYTES = (size_t)2 * G * CUBE * sizeof(T);
+    static constexpr size_t LDS_BYTES = (size_t)G * CUBE * sizeof(T);
 };
+
+// K consecutive words of type T from/to global memory at word alignment, as the widest
+// accesses the hardware takes at that alignment (vectors of 2 and 4 words declared with the
+// alignment of one word become dwordx2 / dwordx4 instructions).
+template <typename T, int W> struct WordVec {
+    typedef T type __attribute__((ext_vector_type(W), aligned(sizeof(T))));
+};
+template <bool NT, typename T, int K>
+__device__ __forceinline__ void load_words(const T *p, T (&out)[K])
+{
+    typedef typename WordVec<T, 4>::type v4;
+    typedef typename WordVec<T, 2>::type v2;
+    int q = 0;
+#pragma unroll
+    for (; q + 4 <= K; q += 4) {
+        const v4 *pv = reinterpret_cast<const v4 *>(p + q);
+        v4 t;
+        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
+        out[q] = t[0]; out[q + 1] = t[1]; out[q + 2] = t[2]; out[q + 3] = t[3];
+    }
+    if (q + 2 <= K) {
+        const v2 *pv = reinterpret_cast<const v2 *>(p + q);
+        v2 t;
+        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
+        out[q] = t[0]; out[q + 1] = t[1];
+        q += 2;
+    }
+    if (q < K) out[q] = gload<NT>(p + q);
+}
+template <bool NT, typename T, int K>
+__device__ __forceinline__ void store_words(T *p, const T (&in)[K])
+{
+    typedef typename WordVec<T, 4>::type v4;
+    typedef typename WordVec<T, 2>::type v2;
+    int q = 0;
+#pragma unroll
+    for (; q + 4 <= K; q += 4) {
+        v4 t = {in[q], in[q + 1], in[q + 2], in[q + 3]};
+        v4 *pv = reinterpret_cast<v4 *>(p + q);
+        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
+    }
+    if (q + 2 <= K) {
+        v2 t = {in[q], in[q + 1]};
+        v2 *pv = reinterpret_cast<v2 *>(p + q);
+        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
+        q += 2;
+    }
+    if (q < K) gstore<NT>(p + q, in[q]);
+}
 
 template <typename T, int N, int G, int NW, int HINT>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
@@ -75,54 +132,58 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     using M = Mfma<T>;
     using acc_t = typename M::acc_t;
     constexpr int P2 = Sh::P2, N3 = Sh::N3, TILES = Sh::TILES, TT = Sh::TT, TPW = Sh::TPW;
-    constexpr int KS = Sh::KS, KSF = Sh::KSF, NT = Sh::NT;
+    constexpr int KS = Sh::KS;
     constexpr int PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE;
     constexpr bool LD_NT = (HINT & 1) != 0, ST_NT = (HINT & 2) != 0;
 
     extern __shared__ __align__(16) unsigned char tpo_lds[];
     T *cube = reinterpret_cast<T *>(tpo_lds);
-    T *dpark = cube + G * CUBE;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int lane = tid & 63;
-    const int x = lane & 15;       // column inside a tile; row of the A operand
-    const int g = lane >> 4;       // k index inside a k-step
+    const int x = lane & 15;       // column inside a tile; hardware row of the A operand
+    const int g = lane >> 4;       // lane group
     const long long e0 = (long long)blockIdx.x * G;
     const long long left = num_elems - e0;
     const int nel = left < G ? (int)left : G;
     const size_t base = (size_t)e0 * N3;
 
-    // ---- A operands: the six matrices, zero-padded to 16 x 4*KS, one word per k-step ------
-    T a_fwd[3][KS], a_bwd[3][KS], a_bz[KSF];
+    // Lane group g holds the KS consecutive indices off(g) .. off(g)+KS-1 of the contracted
+    // axis, off(g) = min(g*KS, n-KS): the last groups slide back so that every index stays
+    // inside the cube.  An index is "owned" by the group whose unslid range contains it; the
+    // k-columns of A are zero for indices a group holds but does not own, so nothing is
+    // counted twice, while result rows are simply duplicated (equal values, equal addresses).
+    const int off = (g * KS < N - KS) ? g * KS : N - KS;
+
+    // ---- A operands: the six matrices with rows and k-columns arranged as above ------------
+    T a_fwd[3][KS], a_bwd[3][KS];
     {
+        int grp, reg;
+        M::split(x, grp, reg);                      // hardware row x -> (lane group, register)
+        const int offr = (grp * KS < N - KS) ? grp * KS : N - KS;
+        const bool iok = reg < KS;
+        const int i = iok ? offr + reg : 0;
         const T *S[3] = {Sx, Sy, Sz};
 #pragma unroll
         for (int d = 0; d < 3; ++d) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const int l = 4 * s + g;
-                const bool ok = (x < N) && (l < N);
-                const int xs = ok ? x : 0, ls = ok ? l : 0;
-                const T f = S[d][ls * N + xs];      // forward: Mat[i][l] = S[l][i]
-                const T b = S[d][xs * N + ls];      // backward: Mat[i][l] = S[i][l]
+                const int l = off + s;
+                const bool ok = iok && (l >= g * KS);
+                const T f = S[d][l * N + i];        // forward: Mat[i][l] = S[l][i]
+                const T b = S[d][i * N + l];        // backward: Mat[i][l] = S[i][l]
                 a_fwd[d][s] = ok ? f : T(0);
                 a_bwd[d][s] = ok ? b : T(0);
             }
         }
-#pragma unroll
-        for (int s = 0; s < KSF; ++s) {
-            const int l = M::row(s, g);
-            const bool ok = (x < N) && (l < N);
-            const T b = Sz[(ok ? x : 0) * N + (ok ? l : 0)];
-            a_bz[s] = ok ? b : T(0);
-        }
     }
 
     // ---- per-tile column data --------------------------------------------------------------
-    int b0[TPW], b1[TPW], b2[TPW];     // LDS offsets of (row 0, column X) for the three axes
+    int b0[TPW], b1[TPW], b2[TPW];     // LDS offsets of (off, column X) for the three axes
     bool colok[TPW];
-    size_t gcol[TPW];                  // word offset of (row 0, column X) in u / v
+    size_t g2[TPW];                    // u / v: word offset of (a, b, off) with (a,b) = X
+    size_t g0[TPW];                    // D: word offset of (off, b, c) with (b,c) = X
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
         const int tt = wave + NW * j;
@@ -130,137 +191,119 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
         const int t = tt - ge * TILES;
         int X = 16 * t + x;
         colok[j] = (tt < TT) && (X < P2) && (ge < nel);
-        if (!colok[j]) { ge = 0; X = 0; }
+        if (!colok[j]) { ge = 0; X = 0; }           // a valid column whose results are dropped
         const int hi = X / N, lo = X - hi * N;
-        b0[j] = ge * CUBE + hi * PB + lo;
-        b1[j] = ge * CUBE + hi * PA + lo;
-        b2[j] = ge * CUBE + hi * PA + lo * PB;
-        gcol[j] = base + (size_t)ge * N3 + (size_t)X;
+        b0[j] = ge * CUBE + hi * PB + lo + off * PA;
+        b1[j] = ge * CUBE + hi * PA + lo + off * PB;
+        b2[j] = ge * CUBE + hi * PA + lo * PB + off;
+        g2[j] = base + (size_t)ge * N3 + (size_t)(X * N + off);
+        g0[j] = base + (size_t)ge * N3 + (size_t)(X + off * P2);
     }
 
-    // ---- D_e: HBM -> registers now, -> LDS after forward axis 0 has been issued -----------
-    constexpr int DIT = (G * N3 + NT - 1) / NT;
-    T dreg[DIT];
+    // ---- D_e in accumulator layout of the axis-0 products, prefetched ------------------------
+    T dreg[TPW][KS];
 #pragma unroll
-    for (int k = 0; k < DIT; ++k) {
-        const int w = tid + k * NT;
-        dreg[k] = (w < nel * N3) ? gload<LD_NT>(D + base + w) : T(0);
-    }
+    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+        for (int r = 0; r < KS; ++r) dreg[j][r] = gload<LD_NT>(D + g0[j] + (size_t)(r * P2));
 
-    // ---- forward axis 0: B from HBM, result to LDS ----------------------------------------
+    // Every product below is written as: all B operands of the wavefront's tiles, then the
+    // MFMAs with the k-step outermost (so that consecutive MFMAs belong to different tiles and
+    // never wait on each other), then all stores.
+#define TPO_MMA_ALL(ACC, AOP, BOP)                                            \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s)                            \
+        _Pragma("unroll") for (int j = 0; j < TPW; ++j)                       \
+            ACC[j] = M::mma(AOP[s], BOP, ACC[j]);
+
+    acc_t acc[TPW];
+    T bv[TPW][KS];
+
+    // ---- forward axis 2: B from HBM (one contiguous chunk per lane), result to LDS ---------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        T bv[KS];
+    for (int j = 0; j < TPW; ++j) load_words<LD_NT>(u + g2[j], bv[j]);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int l = 4 * s + g;
-            const bool ok = colok[j] && (l < N);
-            bv[s] = ok ? gload<LD_NT>(u + gcol[j] + (size_t)((ok ? l : 0) * P2)) : T(0);
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_fwd[2], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+        if (colok[j]) {
+#pragma unroll
+            for (int r = 0; r < KS; ++r) cube[b2[j] + r] = acc[j][r];
         }
-        acc_t acc = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) acc = M::mma(a_fwd[0][s], bv[s], acc);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            if (i < N && colok[j]) cube[b0[j] + i * PA] = acc[r];
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < DIT; ++k) {
-        const int w = tid + k * NT;
-        if (w < G * N3) dpark[lds_index<T, N, G>(w)] = dreg[k];
-    }
     __syncthreads();
 
     // ---- forward axis 1: LDS -> LDS -----------------------------------------------------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        T bv[KS];
+    for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int l = 4 * s + g;
-            bv[s] = (l < N) ? cube[b1[j] + (l < N ? l : 0) * PB] : T(0);
+        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_fwd[1], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+        if (colok[j]) {
+#pragma unroll
+            for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
         }
-        acc_t acc = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) acc = M::mma(a_fwd[1][s], bv[s], acc);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            if (i < N && colok[j]) cube[b1[j] + i * PB] = acc[r];
-        }
-    }
     __syncthreads();
 
-    // ---- forward axis 2, scale by D_e, backward axis 2 (register to register) ---------------
+    // ---- forward axis 0, scale by D_e, backward axis 0 (register to register) ----------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        T bv[KS];
+    for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int l = 4 * s + g;
-            bv[s] = (l < N) ? cube[b2[j] + (l < N ? l : 0)] : T(0);
+        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b0[j] + s * PA];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_fwd[0], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) bv[j][s] = acc[j][s] * dreg[j][s];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_bwd[0], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+        if (colok[j]) {
+#pragma unroll
+            for (int r = 0; r < KS; ++r) cube[b0[j] + r * PA] = acc[j][r];
         }
-        acc_t acc = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) acc = M::mma(a_fwd[2][s], bv[s], acc);
-        T gv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            const T dval = (i < N) ? dpark[b2[j] + (i < N ? i : 0)] : T(0);
-            gv[r] = acc[r] * dval;      // rows >= n are zero on both sides
-        }
-        acc_t acc2 = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KSF; ++s) acc2 = M::mma(a_bz[s], gv[s], acc2);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            if (i < N && colok[j]) cube[b2[j] + i] = acc2[r];
-        }
-    }
     __syncthreads();
 
     // ---- backward axis 1: LDS -> LDS ----------------------------------------------------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        T bv[KS];
+    for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int l = 4 * s + g;
-            bv[s] = (l < N) ? cube[b1[j] + (l < N ? l : 0) * PB] : T(0);
+        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_bwd[1], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+        if (colok[j]) {
+#pragma unroll
+            for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
         }
-        acc_t acc = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) acc = M::mma(a_bwd[1][s], bv[s], acc);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            if (i < N && colok[j]) cube[b1[j] + i * PB] = acc[r];
-        }
-    }
     __syncthreads();
 
-    // ---- backward axis 0: LDS -> HBM ------------------------------------------------------------
+    // ---- backward axis 2: LDS -> HBM (one contiguous chunk per lane) -----------------------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        T bv[KS];
+    for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int l = 4 * s + g;
-            bv[s] = (l < N) ? cube[b0[j] + (l < N ? l : 0) * PA] : T(0);
+        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b2[j] + s];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
+    TPO_MMA_ALL(acc, a_bwd[2], bv[j][s])
+#pragma unroll
+    for (int j = 0; j < TPW; ++j)
+        if (colok[j]) {
+            T vc[KS];
+#pragma unroll
+            for (int r = 0; r < KS; ++r) vc[r] = acc[j][r];
+            store_words<ST_NT>(v + g2[j], vc);
         }
-        acc_t acc = {0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) acc = M::mma(a_bwd[0][s], bv[s], acc);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = M::row(r, g);
-            if (i < N && colok[j]) gstore<ST_NT>(v + gcol[j] + (size_t)(i * P2), acc[r]);
-        }
-    }
+#undef TPO_MMA_ALL
 }
 
 template <typename T, int N, int G, int NW, int HINT>
