@@ -122,7 +122,11 @@ __device__ __forceinline__ void store_words(T *p, const T (&in)[K])
     if (q < K) gstore<NT>(p + q, in[q]);
 }
 
-template <typename T, int N, int G, int NW, int HINT>
+// PERSIST = false: one workgroup per batch of G elements (grid = number of batches).
+// PERSIST = true : a fixed grid of workgroups walks over the batches (batch = blockIdx.x,
+// + gridDim.x, ...) and loads the next batch's u_e and D_e into registers while the current
+// one is being computed, so that no workgroup ever sits idle waiting for its first loads.
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
 ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy,
                   const T *__restrict__ Sz, const T *__restrict__ D, T *v,
@@ -144,10 +148,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     const int lane = tid & 63;
     const int x = lane & 15;       // column inside a tile; hardware row of the A operand
     const int g = lane >> 4;       // lane group
-    const long long e0 = (long long)blockIdx.x * G;
-    const long long left = num_elems - e0;
-    const int nel = left < G ? (int)left : G;
-    const size_t base = (size_t)e0 * N3;
+    const long long nbatch = (num_elems + G - 1) / G;
 
     // Lane group g holds the KS consecutive indices off(g) .. off(g)+KS-1 of the contracted
     // axis, off(g) = min(g*KS, n-KS): the last groups slide back so that every index stays
@@ -179,33 +180,52 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
         }
     }
 
-    // ---- per-tile column data --------------------------------------------------------------
+    // ---- per-tile column data (the same for every batch) -----------------------------------
     int b0[TPW], b1[TPW], b2[TPW];     // LDS offsets of (off, column X) for the three axes
-    bool colok[TPW];
-    size_t g2[TPW];                    // u / v: word offset of (a, b, off) with (a,b) = X
-    size_t g0[TPW];                    // D: word offset of (off, b, c) with (b,c) = X
+    int o2[TPW], o0[TPW];              // word offsets inside the batch: (a,b,off) / (off,b,c)
+    int o2z[TPW], o0z[TPW];            // the same for element 0 of the batch
+    int gel[TPW];                      // element slot of the tile (uniform over the wavefront)
+    bool colst[TPW];                   // the lane's column exists in a full batch
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
         const int tt = wave + NW * j;
         int ge = tt / TILES;
         const int t = tt - ge * TILES;
         int X = 16 * t + x;
-        colok[j] = (tt < TT) && (X < P2) && (ge < nel);
-        if (!colok[j]) { ge = 0; X = 0; }           // a valid column whose results are dropped
+        colst[j] = (tt < TT) && (X < P2);
+        if (!colst[j]) { ge = 0; X = 0; }           // a valid column whose results are dropped
+        gel[j] = ge;
         const int hi = X / N, lo = X - hi * N;
         b0[j] = ge * CUBE + hi * PB + lo + off * PA;
         b1[j] = ge * CUBE + hi * PA + lo + off * PB;
         b2[j] = ge * CUBE + hi * PA + lo * PB + off;
-        g2[j] = base + (size_t)ge * N3 + (size_t)(X * N + off);
-        g0[j] = base + (size_t)ge * N3 + (size_t)(X + off * P2);
+        o2z[j] = X * N + off;
+        o0z[j] = X + off * P2;
+        o2[j] = ge * N3 + o2z[j];
+        o0[j] = ge * N3 + o0z[j];
     }
 
-    // ---- D_e in accumulator layout of the axis-0 products, prefetched ------------------------
-    T dreg[TPW][KS];
+    T un[TPW][KS];      // u_e chunks of the batch about to be computed (B operands, axis 2)
+    T dreg[TPW][KS];    // D_e in the accumulator layout of the axis-0 products
+
+    // Loads of one batch; tiles of element slots beyond the end of the field read slot 0.
+    auto load_u = [&](long long batch) {
+        const long long left = num_elems - batch * G;
+        const T *ub = u + (size_t)batch * (size_t)(G * N3);
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
+        for (int j = 0; j < TPW; ++j)
+            load_words<LD_NT>(ub + (gel[j] < left ? o2[j] : o2z[j]), un[j]);
+    };
+    auto load_d = [&](long long batch) {
+        const long long left = num_elems - batch * G;
+        const T *db = D + (size_t)batch * (size_t)(G * N3);
 #pragma unroll
-        for (int r = 0; r < KS; ++r) dreg[j][r] = gload<LD_NT>(D + g0[j] + (size_t)(r * P2));
+        for (int j = 0; j < TPW; ++j) {
+            const T *dp = db + (gel[j] < left ? o0[j] : o0z[j]);
+#pragma unroll
+            for (int r = 0; r < KS; ++r) dreg[j][r] = gload<LD_NT>(dp + r * P2);
+        }
+    };
 
     // Every product below is written as: all B operands of the wavefront's tiles, then the
     // MFMAs with the k-step outermost (so that consecutive MFMAs belong to different tiles and
@@ -214,119 +234,155 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     _Pragma("unroll") for (int s = 0; s < KS; ++s)                            \
         _Pragma("unroll") for (int j = 0; j < TPW; ++j)                       \
             ACC[j] = M::mma(AOP[s], BOP, ACC[j]);
+#define TPO_ZERO_ACC(ACC) \
+    _Pragma("unroll") for (int j = 0; j < TPW; ++j) ACC[j] = acc_t{0, 0, 0, 0};
 
-    acc_t acc[TPW];
-    T bv[TPW][KS];
+    long long batch = blockIdx.x;
+    if (batch >= nbatch) return;
+    load_u(batch);
+    load_d(batch);
 
-    // ---- forward axis 2: B from HBM (one contiguous chunk per lane), result to LDS ---------
+    for (;;) {
+        const long long left = num_elems - batch * G;
+        const long long next = PERSIST ? batch + gridDim.x : nbatch;
+        bool colok[TPW];
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) load_words<LD_NT>(u + g2[j], bv[j]);
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_fwd[2], bv[j][s])
-#pragma unroll
-    for (int j = 0; j < TPW; ++j)
-        if (colok[j]) {
-#pragma unroll
-            for (int r = 0; r < KS; ++r) cube[b2[j] + r] = acc[j][r];
-        }
-    __syncthreads();
+        for (int j = 0; j < TPW; ++j) colok[j] = colst[j] && (gel[j] < left);
 
-    // ---- forward axis 1: LDS -> LDS -----------------------------------------------------------
-#pragma unroll
-    for (int j = 0; j < TPW; ++j)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_fwd[1], bv[j][s])
-#pragma unroll
-    for (int j = 0; j < TPW; ++j)
-        if (colok[j]) {
-#pragma unroll
-            for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
-        }
-    __syncthreads();
+        acc_t acc[TPW];
+        T bv[TPW][KS];
 
-    // ---- forward axis 0, scale by D_e, backward axis 0 (register to register) ----------------
+        // ---- forward axis 2: B = u_e chunks (registers), result to LDS ----------------------
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_fwd[2], un[j][s])
+        if (PERSIST && next < nbatch) load_u(next);     // next batch's u_e, in flight from here
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
+        for (int j = 0; j < TPW; ++j)
+            if (colok[j]) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b0[j] + s * PA];
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_fwd[0], bv[j][s])
-#pragma unroll
-    for (int j = 0; j < TPW; ++j)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) bv[j][s] = acc[j][s] * dreg[j][s];
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_bwd[0], bv[j][s])
-#pragma unroll
-    for (int j = 0; j < TPW; ++j)
-        if (colok[j]) {
-#pragma unroll
-            for (int r = 0; r < KS; ++r) cube[b0[j] + r * PA] = acc[j][r];
-        }
-    __syncthreads();
+                for (int r = 0; r < KS; ++r) cube[b2[j] + r] = acc[j][r];
+            }
+        __syncthreads();
 
-    // ---- backward axis 1: LDS -> LDS ----------------------------------------------------------
+        // ---- forward axis 1: LDS -> LDS -------------------------------------------------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
+        for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
+            for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_fwd[1], bv[j][s])
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_bwd[1], bv[j][s])
+        for (int j = 0; j < TPW; ++j)
+            if (colok[j]) {
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
-        if (colok[j]) {
-#pragma unroll
-            for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
-        }
-    __syncthreads();
+                for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
+            }
+        __syncthreads();
 
-    // ---- backward axis 2: LDS -> HBM (one contiguous chunk per lane) -----------------------------
+        // ---- forward axis 0, scale by D_e, backward axis 0 (register to register) ------------
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
+        for (int j = 0; j < TPW; ++j)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) bv[j][s] = cube[b2[j] + s];
+            for (int s = 0; s < KS; ++s) bv[j][s] = cube[b0[j] + s * PA];
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_fwd[0], bv[j][s])
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) acc[j] = acc_t{0, 0, 0, 0};
-    TPO_MMA_ALL(acc, a_bwd[2], bv[j][s])
+        for (int j = 0; j < TPW; ++j)
 #pragma unroll
-    for (int j = 0; j < TPW; ++j)
-        if (colok[j]) {
-            T vc[KS];
+            for (int s = 0; s < KS; ++s) bv[j][s] = acc[j][s] * dreg[j][s];
+        if (PERSIST && next < nbatch) load_d(next);     // next batch's D_e
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_bwd[0], bv[j][s])
 #pragma unroll
-            for (int r = 0; r < KS; ++r) vc[r] = acc[j][r];
-            store_words<ST_NT>(v + g2[j], vc);
-        }
+        for (int j = 0; j < TPW; ++j)
+            if (colok[j]) {
+#pragma unroll
+                for (int r = 0; r < KS; ++r) cube[b0[j] + r * PA] = acc[j][r];
+            }
+        __syncthreads();
+
+        // ---- backward axis 1: LDS -> LDS -------------------------------------------------------
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_bwd[1], bv[j][s])
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+            if (colok[j]) {
+#pragma unroll
+                for (int r = 0; r < KS; ++r) cube[b1[j] + r * PB] = acc[j][r];
+            }
+        __syncthreads();
+
+        // ---- backward axis 2: LDS -> HBM (one contiguous chunk per lane) -----------------------
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) bv[j][s] = cube[b2[j] + s];
+        TPO_ZERO_ACC(acc)
+        TPO_MMA_ALL(acc, a_bwd[2], bv[j][s])
+        T *vb = v + (size_t)batch * (size_t)(G * N3);
+#pragma unroll
+        for (int j = 0; j < TPW; ++j)
+            if (colok[j]) {
+                T vc[KS];
+#pragma unroll
+                for (int r = 0; r < KS; ++r) vc[r] = acc[j][r];
+                store_words<ST_NT>(vb + o2[j], vc);
+            }
+
+        if (!PERSIST || next >= nbatch) break;
+        batch = next;
+        __syncthreads();        // all reads of the cube are done before the next batch writes it
+    }
 #undef TPO_MMA_ALL
+#undef TPO_ZERO_ACC
 }
 
-template <typename T, int N, int G, int NW, int HINT>
+// Persistent grids are sized from the occupancy the runtime reports for the kernel.
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST>
 struct MfmaLauncher {
     using Sh = MfmaShape<T, N, G, NW>;
+    static inline int wgs_per_device = 0;
 
     static hipError_t launch(const ApplyArgs &a)
     {
-        const long long blocks = (a.num_elems + G - 1) / G;
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT>), dim3((unsigned)blocks),
-                           dim3(Sh::NT), Sh::LDS_BYTES, a.stream, (const T *)a.u,
-                           (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
+        const long long nbatch = (a.num_elems + G - 1) / G;
+        if (nbatch <= 0 || nbatch > 0x7fffffffLL) return hipErrorInvalidValue;
+        long long blocks = nbatch;
+        if (PERSIST) {
+            if (wgs_per_device <= 0) return hipErrorNotInitialized;
+            if (blocks > wgs_per_device) blocks = wgs_per_device;
+        }
+        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST>),
+                           dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
+                           (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
         return hipGetLastError();
     }
 
     static hipError_t prepare()
     {
-        if (Sh::LDS_BYTES <= 48 * 1024) return hipSuccess;
-        return hipFuncSetAttribute((const void *)ihelm_mfma_kernel<T, N, G, NW, HINT>,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Sh::LDS_BYTES);
+        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST>;
+        if (Sh::LDS_BYTES > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)Sh::LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
+        if (PERSIST) {
+            int dev = 0, cus = 0, per_cu = 0;
+            hipError_t e = hipGetDevice(&dev);
+            if (e != hipSuccess) return e;
+            e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return e;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, Sh::NT, Sh::LDS_BYTES);
+            if (e != hipSuccess) return e;
+            if (per_cu < 1) per_cu = 1;
+            wgs_per_device = cus * per_cu;
+        }
+        return hipSuccess;
     }
 };
 

@@ -11,14 +11,15 @@ struct MfmaTune_f32 {
     static constexpr int G = (8 + TILES - 1) / TILES;
     static constexpr int NW = 4;
     static constexpr int HINT = 2;
+    static constexpr bool PERSIST = false;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT>::launch,                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST>::launch,                                   \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT>::prepare                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f32(int n)

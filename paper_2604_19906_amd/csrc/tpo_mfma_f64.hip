@@ -11,14 +11,25 @@ struct MfmaTune_f64 {
     static constexpr int G = (8 + TILES - 1) / TILES;
     static constexpr int NW = 4;
     static constexpr int HINT = 2;
+    static constexpr bool PERSIST = false;
+};
+
+// n = 16: persistent grid with register prefetch of the next element, plain loads and stores
+// (1.24 ms against 1.30-1.38 ms for one workgroup per element, 65536 elements).
+template <>
+struct MfmaTune_f64<16> {
+    static constexpr int G = 1;
+    static constexpr int NW = 4;
+    static constexpr int HINT = 0;
+    static constexpr bool PERSIST = true;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT>::launch,                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST>::launch,                                   \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT>::prepare                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f64(int n)
