@@ -73,55 +73,6 @@ struct MfmaShape {
     static constexpr size_t LDS_BYTES = (size_t)G * CUBE * sizeof(T);
 };
 
-// K consecutive words of type T from/to global memory at word alignment, as the widest
-// accesses the hardware takes at that alignment (vectors of 2 and 4 words declared with the
-// alignment of one word become dwordx2 / dwordx4 instructions).
-template <typename T, int W> struct WordVec {
-    typedef T type __attribute__((ext_vector_type(W), aligned(sizeof(T))));
-};
-template <bool NT, typename T, int K>
-__device__ __forceinline__ void load_words(const T *p, T (&out)[K])
-{
-    typedef typename WordVec<T, 4>::type v4;
-    typedef typename WordVec<T, 2>::type v2;
-    int q = 0;
-#pragma unroll
-    for (; q + 4 <= K; q += 4) {
-        const v4 *pv = reinterpret_cast<const v4 *>(p + q);
-        v4 t;
-        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
-        out[q] = t[0]; out[q + 1] = t[1]; out[q + 2] = t[2]; out[q + 3] = t[3];
-    }
-    if (q + 2 <= K) {
-        const v2 *pv = reinterpret_cast<const v2 *>(p + q);
-        v2 t;
-        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
-        out[q] = t[0]; out[q + 1] = t[1];
-        q += 2;
-    }
-    if (q < K) out[q] = gload<NT>(p + q);
-}
-template <bool NT, typename T, int K>
-__device__ __forceinline__ void store_words(T *p, const T (&in)[K])
-{
-    typedef typename WordVec<T, 4>::type v4;
-    typedef typename WordVec<T, 2>::type v2;
-    int q = 0;
-#pragma unroll
-    for (; q + 4 <= K; q += 4) {
-        v4 t = {in[q], in[q + 1], in[q + 2], in[q + 3]};
-        v4 *pv = reinterpret_cast<v4 *>(p + q);
-        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
-    }
-    if (q + 2 <= K) {
-        v2 t = {in[q], in[q + 1]};
-        v2 *pv = reinterpret_cast<v2 *>(p + q);
-        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
-        q += 2;
-    }
-    if (q < K) gstore<NT>(p + q, in[q]);
-}
-
 // PERSIST = false: one workgroup per batch of G elements (grid = number of batches).
 // PERSIST = true : a fixed grid of workgroups walks over the batches (batch = blockIdx.x,
 // + gridDim.x, ...) and loads the next batch's u_e and D_e into registers while the current

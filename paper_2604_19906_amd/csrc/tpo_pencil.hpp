@@ -108,8 +108,80 @@ __device__ __forceinline__ void gstore(T *p, T x)
     else *p = x;
 }
 
+// K consecutive words of type T from/to global memory at word alignment, as the widest
+// accesses the hardware takes at that alignment (vectors of 2 and 4 words declared with the
+// alignment of one word become dwordx2 / dwordx4 instructions).
+template <typename T, int W> struct WordVec {
+    typedef T type __attribute__((ext_vector_type(W), aligned(sizeof(T))));
+};
+template <bool NT, typename T, int K>
+__device__ __forceinline__ void load_words(const T *p, T (&out)[K])
+{
+    typedef typename WordVec<T, 4>::type v4;
+    typedef typename WordVec<T, 2>::type v2;
+    int q = 0;
+#pragma unroll
+    for (; q + 4 <= K; q += 4) {
+        const v4 *pv = reinterpret_cast<const v4 *>(p + q);
+        v4 t;
+        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
+        out[q] = t[0]; out[q + 1] = t[1]; out[q + 2] = t[2]; out[q + 3] = t[3];
+    }
+    if (q + 2 <= K) {
+        const v2 *pv = reinterpret_cast<const v2 *>(p + q);
+        v2 t;
+        if constexpr (NT) t = __builtin_nontemporal_load(pv); else t = *pv;
+        out[q] = t[0]; out[q + 1] = t[1];
+        q += 2;
+    }
+    if (q < K) out[q] = gload<NT>(p + q);
+}
+template <bool NT, typename T, int K>
+__device__ __forceinline__ void store_words(T *p, const T (&in)[K])
+{
+    typedef typename WordVec<T, 4>::type v4;
+    typedef typename WordVec<T, 2>::type v2;
+    int q = 0;
+#pragma unroll
+    for (; q + 4 <= K; q += 4) {
+        v4 t = {in[q], in[q + 1], in[q + 2], in[q + 3]};
+        v4 *pv = reinterpret_cast<v4 *>(p + q);
+        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
+    }
+    if (q + 2 <= K) {
+        v2 t = {in[q], in[q + 1]};
+        v2 *pv = reinterpret_cast<v2 *>(p + q);
+        if constexpr (NT) __builtin_nontemporal_store(t, pv); else *pv = t;
+        q += 2;
+    }
+    if (q < K) gstore<NT>(p + q, in[q]);
+}
+
 // HINT bit 0: non-temporal loads of u and D; bit 1: non-temporal stores of v.
-template <typename T, int N, int G, int HINT>
+// DDIRECT = false: D_e is loaded coalesced with u_e and parked in LDS until the scale.
+// DDIRECT = true : every lane loads, at kernel start, the n consecutive words of D_e that
+//                  belong to its axis-2 pencil (no LDS for D_e: half the LDS per workgroup).
+// XCD = true : workgroups are renumbered so that each of the 8 accelerator dies (workgroups
+//              are dealt to them round-robin) works on one contiguous eighth of the elements;
+//              cache lines shared by neighbouring elements then stay within one L2.
+//              The grid must be pencil_grid<XCD>(number of batches).
+template <bool XCD>
+__host__ __device__ inline long long pencil_grid(long long nbatch)
+{
+    return XCD ? 8 * ((nbatch + 7) / 8) : nbatch;
+}
+template <bool XCD>
+__device__ __forceinline__ long long pencil_batch(long long nbatch)
+{
+    if constexpr (XCD) {
+        const long long per = (nbatch + 7) / 8;
+        return (long long)(blockIdx.x & 7) * per + (long long)(blockIdx.x >> 3);
+    } else {
+        return blockIdx.x;
+    }
+}
+
+template <typename T, int N, int G, int HINT, bool DDIRECT = false, bool XCD = false>
 __global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
 ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
                     const T *__restrict__ D, T *v, long long num_elems)
@@ -129,7 +201,10 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     const int p = tid - g * P;      // pencil id inside the element
     const int hi = p / N;
     const int lo = p - hi * N;
-    const long long e = (long long)blockIdx.x * G + g;
+    const long long nbatch = (num_elems + G - 1) / G;
+    const long long batch = pencil_batch<XCD>(nbatch);
+    if (XCD && batch >= nbatch) return;                 // whole workgroup: no barrier is skipped
+    const long long e = batch * G + g;
     const bool on = (tid < G * P) && (e < num_elems);
 
     T *cube = cube_all + (g < G ? g : 0) * CUBE;
@@ -139,17 +214,23 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     T x[N], y[N];
 
     // forward, axis 0: lane (b,c) = (hi,lo); global reads are consecutive over lanes
+    T dd[N];
     if (on) {
-        T dd[N];
 #pragma unroll
         for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base + (size_t)(l * P + p));
+        if constexpr (DDIRECT) {
+            load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);   // D_e[a][b][0..n-1]
+        } else {
 #pragma unroll
-        for (int l = 0; l < N; ++l) dd[l] = gload<(HINT & 1) != 0>(D + base + (size_t)(l * P + p));
+            for (int l = 0; l < N; ++l) dd[l] = gload<(HINT & 1) != 0>(D + base + (size_t)(l * P + p));
+        }
         mode_product<T, N, true>(Sx, x, y);
 #pragma unroll
         for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
+        if constexpr (!DDIRECT) {
 #pragma unroll
-        for (int l = 0; l < N; ++l) dpark[l * PA + hi * PB + lo] = dd[l];
+            for (int l = 0; l < N; ++l) dpark[l * PA + hi * PB + lo] = dd[l];
+        }
     }
     __syncthreads();
 
@@ -169,7 +250,7 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
         for (int q = 0; q < N; ++q) x[q] = cube[hi * PA + lo * PB + q];
         mode_product<T, N, true>(Sz, x, y);
 #pragma unroll
-        for (int k = 0; k < N; ++k) y[k] *= dpark[hi * PA + lo * PB + k];
+        for (int k = 0; k < N; ++k) y[k] *= DDIRECT ? dd[k] : dpark[hi * PA + lo * PB + k];
         mode_product<T, N, false>(Sz, y, x);
 #pragma unroll
         for (int k = 0; k < N; ++k) cube[hi * PA + lo * PB + k] = x[k];
@@ -371,42 +452,63 @@ ihelm_pencil_flat_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     }
 }
 
-// Elements per workgroup and hint bits per (type, n).  The defaults are the lane-utilisation
-// rule and non-temporal stores; the specialisations are the best of a sweep on MI355X over
-// G in {1,2,4,8} and the four hint combinations at the sizes of the named workloads.
+// Per (type, n): elements per workgroup, hint bits, how D_e is brought in, and whether the
+// workgroups are renumbered per accelerator die.  Defaults: the lane-utilisation rule for G,
+// non-temporal stores, D_e loaded straight into its pencil layout (half the LDS), and the
+// renumbering whenever an element is not a whole number of 128-byte lines.  The
+// specialisations are the best of sweeps on MI355X at the sizes of the named workloads
+// (G in {1,2,4,8} x hint bits x D mode x renumbering).
 template <typename T, int N>
 struct PencilTune {
     static constexpr int G = pencil_group<T, N>();
     static constexpr int HINT = 2;
+    static constexpr bool DDIRECT = true;
+    static constexpr bool XCD = (N * N * N * sizeof(T)) % 128 != 0;
 };
-template <> struct PencilTune<double, 8> { static constexpr int G = 4, HINT = 3; };
-template <> struct PencilTune<double, 11> { static constexpr int G = 1, HINT = 2; };
-template <> struct PencilTune<double, 16> { static constexpr int G = 1, HINT = 3; };
-template <> struct PencilTune<float, 13> { static constexpr int G = 3, HINT = 0; };
+template <> struct PencilTune<double, 8> {
+    static constexpr int G = 4, HINT = 3;
+    static constexpr bool DDIRECT = false, XCD = false;
+};
+template <> struct PencilTune<double, 11> {
+    static constexpr int G = 1, HINT = 0;
+    static constexpr bool DDIRECT = true, XCD = true;
+};
+template <> struct PencilTune<double, 16> {
+    static constexpr int G = 1, HINT = 2;
+    static constexpr bool DDIRECT = true, XCD = false;
+};
+template <> struct PencilTune<float, 13> {
+    static constexpr int G = 3, HINT = 0;
+    static constexpr bool DDIRECT = true, XCD = false;
+};
 
 template <typename T, int N>
 struct PencilLauncher {
-    static constexpr int G = PencilTune<T, N>::G;
-    static constexpr int HINT = PencilTune<T, N>::HINT;
+    using Tune = PencilTune<T, N>;
+    static constexpr int G = Tune::G;
     using Sh = PencilShape<T, N, G>;
+    static constexpr size_t LDS = Tune::DDIRECT ? Sh::LDS_BYTES / 2 : Sh::LDS_BYTES;
+
+    static constexpr auto kernel()
+    {
+        return &ihelm_pencil_kernel<T, N, G, Tune::HINT, Tune::DDIRECT, Tune::XCD>;
+    }
 
     static hipError_t launch(const ApplyArgs &a)
     {
-        const long long blocks = (a.num_elems + G - 1) / G;
+        const long long blocks = pencil_grid<Tune::XCD>((a.num_elems + G - 1) / G);
         if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((ihelm_pencil_kernel<T, N, G, HINT>), dim3((unsigned)blocks),
-                           dim3(Sh::NT), Sh::LDS_BYTES, a.stream, (const T *)a.u,
-                           (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
+        hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
+                           (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
         return hipGetLastError();
     }
 
     static hipError_t prepare()
     {
-        if (Sh::LDS_BYTES <= 48 * 1024) return hipSuccess;
-        return hipFuncSetAttribute((const void *)ihelm_pencil_kernel<T, N, G, HINT>,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)Sh::LDS_BYTES);
+        if (LDS <= 48 * 1024) return hipSuccess;
+        return hipFuncSetAttribute((const void *)kernel(),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
     }
 };
 
