@@ -98,7 +98,7 @@ def main() -> int:
     variant = {"auto": tpo.TPO_VARIANT_AUTO, "pencil": tpo.TPO_VARIANT_PENCIL,
                "mfma": tpo.TPO_VARIANT_MFMA}[args.variant]
     dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
-    chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt)
+    chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt, not w.distinct_s)
     chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma"}[chosen]
 
     # ---- inputs: seeded, generated block by block on the host, resident in HBM -------------

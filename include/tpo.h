@@ -101,12 +101,16 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
                             const void *D, void *v, int n, long long num_elems, int dtype,
                             void *stream, int variant);
 
-/* tpo_ihelm_variant_for -- which family TPO_VARIANT_AUTO selects for (n, dtype):
- * TPO_VARIANT_PENCIL or TPO_VARIANT_MFMA, or TPO_ERR_UNSUPPORTED / TPO_ERR_INVALID_ARG.
+/* tpo_ihelm_variant_for -- which family TPO_VARIANT_AUTO selects for (n, dtype).
+ * shared_s != 0 asks about calls that pass ONE matrix for all three directions (S_x, S_y and
+ * S_z are the same pointer), 0 about calls with distinct pointers; the choice can differ
+ * because the matrix-core kernels hold a shared matrix once.
+ * Returns TPO_VARIANT_PENCIL or TPO_VARIANT_MFMA, or TPO_ERR_UNSUPPORTED / TPO_ERR_INVALID_ARG.
  * Pure host function; needs no device. */
-int tpo_ihelm_variant_for(int n, int dtype);
+int tpo_ihelm_variant_for(int n, int dtype, int shared_s);
 
-/* tpo_ihelm_has_variant -- 1 if `variant` has a kernel for (n, dtype), else 0. */
+/* tpo_ihelm_has_variant -- 1 if `variant` has a kernel for (n, dtype), else 0
+ * (TPO_VARIANT_AUTO always has one for supported n). */
 int tpo_ihelm_has_variant(int n, int dtype, int variant);
 
 /*

@@ -15,13 +15,13 @@ std::mutex g_mu;
 int g_refs[kMaxDevices] = {0};
 
 // Family chosen by TPO_VARIANT_AUTO, from measurements on MI355X (see profiles/).
-int auto_variant(int n, int dtype)
+int auto_variant(int n, int dtype, bool shared_s)
 {
     // Measured on MI355X at the sizes of the named workloads (ms per launch, pencil / MFMA):
-    // fp64 n=8 0.25 / 0.27, n=11 1.46 / 1.69, n=16 1.19 / 1.24, fp32 n=13 5.99 / 6.22.
-    // The pencil kernel wins or ties everywhere, so it is the default for every size.
-    (void)n;
-    (void)dtype;
+    // fp64 n=8 0.25 / 0.27, n=11 1.46 / 1.69, fp32 n=13 5.99 / 6.09: pencil.
+    // fp64 n=16: pencil 1.19; MFMA 1.16 when one matrix is shared by the three directions
+    // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
+    if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
     return TPO_VARIANT_PENCIL;
 }
 
@@ -78,12 +78,12 @@ int tpo_destroy(void)
     return TPO_OK;
 }
 
-int tpo_ihelm_variant_for(int n, int dtype)
+int tpo_ihelm_variant_for(int n, int dtype, int shared_s)
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
     if (n < 1) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
-    int var = auto_variant(n, dtype);
+    int var = auto_variant(n, dtype, shared_s != 0);
     if (!lookup(n, dtype, var)) var = TPO_VARIANT_PENCIL;
     return var;
 }
@@ -92,7 +92,7 @@ int tpo_ihelm_has_variant(int n, int dtype, int variant)
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return 0;
     if (n < 1 || n > TPO_MAX_N) return 0;
-    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_variant_for(n, dtype);
+    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_variant_for(n, dtype, 0);
     return lookup(n, dtype, variant) != nullptr;
 }
 
@@ -102,7 +102,8 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
 {
     const int rc = tpo::validate_apply(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, variant);
     if (rc != TPO_OK) return rc;
-    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_variant_for(n, dtype);
+    if (variant == TPO_VARIANT_AUTO)
+        variant = tpo_ihelm_variant_for(n, dtype, S_x == S_y && S_y == S_z);
     const tpo::KernelEntry *k = lookup(n, dtype, variant);
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;

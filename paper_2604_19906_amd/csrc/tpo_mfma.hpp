@@ -77,7 +77,10 @@ struct MfmaShape {
 // PERSIST = true : a fixed grid of workgroups walks over the batches (batch = blockIdx.x,
 // + gridDim.x, ...) and loads the next batch's u_e and D_e into registers while the current
 // one is being computed, so that no workgroup ever sits idle waiting for its first loads.
-template <typename T, int N, int G, int NW, int HINT, bool PERSIST>
+// SAMES = true: the caller passed one matrix for all three directions (equal pointers); the A
+// operands are then held once instead of three times (for n = 16 in fp64 that is 32 VGPRs,
+// the difference between three and four wavefronts per SIMD).
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
 ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy,
                   const T *__restrict__ Sz, const T *__restrict__ D, T *v,
@@ -109,7 +112,8 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     const int off = (g * KS < N - KS) ? g * KS : N - KS;
 
     // ---- A operands: the six matrices with rows and k-columns arranged as above ------------
-    T a_fwd[3][KS], a_bwd[3][KS];
+    constexpr int ND = SAMES ? 1 : 3;           // distinct direction matrices held
+    T a_fwd[ND][KS], a_bwd[ND][KS];
     {
         int grp, reg;
         M::split(x, grp, reg);                      // hardware row x -> (lane group, register)
@@ -118,7 +122,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
         const int i = iok ? offr + reg : 0;
         const T *S[3] = {Sx, Sy, Sz};
 #pragma unroll
-        for (int d = 0; d < 3; ++d) {
+        for (int d = 0; d < ND; ++d) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int l = off + s;
@@ -205,7 +209,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 
         // ---- forward axis 2: B = u_e chunks (registers), result to LDS ----------------------
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_fwd[2], un[j][s])
+        TPO_MMA_ALL(acc, a_fwd[SAMES ? 0 : 2], un[j][s])
         if (PERSIST && next < nbatch) load_u(next);     // next batch's u_e, in flight from here
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
@@ -221,7 +225,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 #pragma unroll
             for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_fwd[1], bv[j][s])
+        TPO_MMA_ALL(acc, a_fwd[SAMES ? 0 : 1], bv[j][s])
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
             if (colok[j]) {
@@ -236,14 +240,14 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 #pragma unroll
             for (int s = 0; s < KS; ++s) bv[j][s] = cube[b0[j] + s * PA];
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_fwd[0], bv[j][s])
+        TPO_MMA_ALL(acc, a_fwd[SAMES ? 0 : 0], bv[j][s])
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
 #pragma unroll
             for (int s = 0; s < KS; ++s) bv[j][s] = acc[j][s] * dreg[j][s];
         if (PERSIST && next < nbatch) load_d(next);     // next batch's D_e
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_bwd[0], bv[j][s])
+        TPO_MMA_ALL(acc, a_bwd[SAMES ? 0 : 0], bv[j][s])
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
             if (colok[j]) {
@@ -258,7 +262,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 #pragma unroll
             for (int s = 0; s < KS; ++s) bv[j][s] = cube[b1[j] + s * PB];
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_bwd[1], bv[j][s])
+        TPO_MMA_ALL(acc, a_bwd[SAMES ? 0 : 1], bv[j][s])
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
             if (colok[j]) {
@@ -273,7 +277,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 #pragma unroll
             for (int s = 0; s < KS; ++s) bv[j][s] = cube[b2[j] + s];
         TPO_ZERO_ACC(acc)
-        TPO_MMA_ALL(acc, a_bwd[2], bv[j][s])
+        TPO_MMA_ALL(acc, a_bwd[SAMES ? 0 : 2], bv[j][s])
         T *vb = v + (size_t)batch * (size_t)(G * N3);
 #pragma unroll
         for (int j = 0; j < TPW; ++j)
@@ -296,27 +300,34 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 template <typename T, int N, int G, int NW, int HINT, bool PERSIST>
 struct MfmaLauncher {
     using Sh = MfmaShape<T, N, G, NW>;
-    static inline int wgs_per_device = 0;
+    static inline int wgs_per_device[2] = {0, 0};       // [SAMES]
 
-    static hipError_t launch(const ApplyArgs &a)
+    template <bool SAMES>
+    static hipError_t launch_as(const ApplyArgs &a)
     {
         const long long nbatch = (a.num_elems + G - 1) / G;
         if (nbatch <= 0 || nbatch > 0x7fffffffLL) return hipErrorInvalidValue;
         long long blocks = nbatch;
         if (PERSIST) {
-            if (wgs_per_device <= 0) return hipErrorNotInitialized;
-            if (blocks > wgs_per_device) blocks = wgs_per_device;
+            if (wgs_per_device[SAMES] <= 0) return hipErrorNotInitialized;
+            if (blocks > wgs_per_device[SAMES]) blocks = wgs_per_device[SAMES];
         }
-        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST>),
+        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES>),
                            dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
         return hipGetLastError();
     }
 
-    static hipError_t prepare()
+    static hipError_t launch(const ApplyArgs &a)
     {
-        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST>;
+        return (a.sx == a.sy && a.sy == a.sz) ? launch_as<true>(a) : launch_as<false>(a);
+    }
+
+    template <bool SAMES>
+    static hipError_t prepare_as()
+    {
+        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES>;
         if (Sh::LDS_BYTES > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)Sh::LDS_BYTES);
@@ -331,9 +342,15 @@ struct MfmaLauncher {
             e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, Sh::NT, Sh::LDS_BYTES);
             if (e != hipSuccess) return e;
             if (per_cu < 1) per_cu = 1;
-            wgs_per_device = cus * per_cu;
+            wgs_per_device[SAMES] = cus * per_cu;
         }
         return hipSuccess;
+    }
+
+    static hipError_t prepare()
+    {
+        hipError_t e = prepare_as<false>();
+        return e != hipSuccess ? e : prepare_as<true>();
     }
 };
 

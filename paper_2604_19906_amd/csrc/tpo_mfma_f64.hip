@@ -14,10 +14,18 @@ struct MfmaTune_f64 {
     static constexpr bool PERSIST = false;
 };
 
-// n = 16: persistent grid with register prefetch of the next element, plain loads and stores
-// (1.24 ms against 1.30-1.38 ms for one workgroup per element, 65536 elements).
+// n = 16: one workgroup per element, plain loads and stores (1.16 ms on 65536 elements with
+// a shared matrix; the persistent form measured 1.24-1.26 ms there).
 template <>
 struct MfmaTune_f64<16> {
+    static constexpr int G = 1;
+    static constexpr int NW = 4;
+    static constexpr int HINT = 0;
+    static constexpr bool PERSIST = false;
+};
+// n = 11: persistent grid with register prefetch of the next element (1.69 ms against 1.87 ms).
+template <>
+struct MfmaTune_f64<11> {
     static constexpr int G = 1;
     static constexpr int NW = 4;
     static constexpr int HINT = 0;

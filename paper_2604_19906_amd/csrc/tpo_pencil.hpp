@@ -277,181 +277,6 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Flat-I/O form of the same kernel.  The workgroup's G elements are one contiguous span of
-// G*n^3 words in each of u, D and v.  The span is moved with 16-byte (VEC words) accesses,
-// lane after lane, regardless of where rows and elements begin: HBM -> registers -> LDS for
-// u and D, LDS -> registers -> HBM for v.  All six mode products then run LDS to LDS.
-// Needs 16-byte aligned arrays and G*n^3 divisible by VEC so that every span starts aligned;
-// the direct kernel above serves every other case.
-template <typename T, int VEC> struct VecOf;
-template <> struct VecOf<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
-template <> struct VecOf<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
-template <> struct VecOf<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
-
-template <typename T, int N, int G>
-__device__ __forceinline__ int lds_index(int w)
-{
-    using Sh = PencilShape<T, N, G>;
-    if constexpr (Sh::CUBE == N * N * N) {
-        return w;                      // odd n: no padding, the span is stored as it is
-    } else {
-        const int g = w / (N * N * N);
-        const int r = w - g * (N * N * N);
-        const int a = r / (N * N);
-        const int bc = r - a * (N * N);
-        const int b = bc / N;
-        const int c = bc - b * N;
-        return g * Sh::CUBE + a * Sh::PA + b * Sh::PB + c;
-    }
-}
-
-template <typename T, int N, int G, int VEC, int HINT>
-__global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
-ihelm_pencil_flat_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
-                         const T *__restrict__ D, T *v, long long num_elems)
-{
-    using Sh = PencilShape<T, N, G>;
-    using V = typename VecOf<T, VEC>::type;
-    constexpr int P = Sh::P, PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE, NT = Sh::NT;
-    constexpr int N3 = N * N * N;
-    constexpr bool PLAIN = (CUBE == N3);                       // unpadded LDS layout
-    constexpr int SPANV = (G * N3 + VEC - 1) / VEC;            // vectors in a full span
-    constexpr int ITER = (SPANV + NT - 1) / NT;                // vectors per lane
-    static_assert((G * N3) % VEC == 0, "span must be a whole number of vectors");
-    extern __shared__ __align__(16) unsigned char tpo_lds[];
-    T *cube_all = reinterpret_cast<T *>(tpo_lds);
-    T *dpark_all = cube_all + G * CUBE;
-
-    const TPO_CONSTANT T *Sx = (const TPO_CONSTANT T *)Sx_;
-    const TPO_CONSTANT T *Sy = (const TPO_CONSTANT T *)Sy_;
-    const TPO_CONSTANT T *Sz = (const TPO_CONSTANT T *)Sz_;
-
-    const int tid = threadIdx.x;
-    const long long e0 = (long long)blockIdx.x * G;
-    const long long left = num_elems - e0;
-    const int nel = left < G ? (int)left : G;                  // elements in this span
-    const int words = nel * N3;
-    const size_t base = (size_t)e0 * N3;
-
-    // ---- span of u and D: HBM -> registers (all loads in flight), then -> LDS -------------
-    {
-        V xu[ITER], xd[ITER];
-#pragma unroll
-        for (int k = 0; k < ITER; ++k) {
-            const int w = (tid + k * NT) * VEC;
-            if (w + VEC <= words) {
-                xu[k] = gload<(HINT & 1) != 0>(reinterpret_cast<const V *>(u + base + w));
-                xd[k] = gload<(HINT & 1) != 0>(reinterpret_cast<const V *>(D + base + w));
-            } else {
-#pragma unroll
-                for (int t = 0; t < VEC; ++t) {             // ragged end of a short last span
-                    xu[k][t] = (w + t < words) ? u[base + w + t] : T(0);
-                    xd[k][t] = (w + t < words) ? D[base + w + t] : T(0);
-                }
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < ITER; ++k) {
-            const int w = (tid + k * NT) * VEC;
-            if (w < G * N3) {
-                if constexpr (PLAIN) {
-                    *reinterpret_cast<V *>(cube_all + w) = xu[k];
-                    *reinterpret_cast<V *>(dpark_all + w) = xd[k];
-                } else {
-#pragma unroll
-                    for (int t = 0; t < VEC; ++t) {
-                        const int idx = lds_index<T, N, G>(w + t);
-                        cube_all[idx] = xu[k][t];
-                        dpark_all[idx] = xd[k][t];
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    const int g = tid / P;
-    const int p = tid - g * P;
-    const int hi = p / N;
-    const int lo = p - hi * N;
-    const bool on = (tid < G * P) && (g < nel);
-    T *cube = cube_all + (g < G ? g : 0) * CUBE;
-    T *dpark = dpark_all + (g < G ? g : 0) * CUBE;
-    T x[N], y[N];
-
-    // forward, axis 0: lane (b,c) = (hi,lo)
-    if (on) {
-#pragma unroll
-        for (int l = 0; l < N; ++l) x[l] = cube[l * PA + hi * PB + lo];
-        mode_product<T, N, true>(Sx, x, y);
-#pragma unroll
-        for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
-    }
-    __syncthreads();
-    // forward, axis 1: lane (a,c) = (hi,lo)
-    if (on) {
-#pragma unroll
-        for (int m = 0; m < N; ++m) x[m] = cube[hi * PA + m * PB + lo];
-        mode_product<T, N, true>(Sy, x, y);
-#pragma unroll
-        for (int j = 0; j < N; ++j) cube[hi * PA + j * PB + lo] = y[j];
-    }
-    __syncthreads();
-    // forward axis 2, diagonal scale, backward axis 2: lane (a,b) = (hi,lo)
-    if (on) {
-#pragma unroll
-        for (int q = 0; q < N; ++q) x[q] = cube[hi * PA + lo * PB + q];
-        mode_product<T, N, true>(Sz, x, y);
-#pragma unroll
-        for (int k = 0; k < N; ++k) y[k] *= dpark[hi * PA + lo * PB + k];
-        mode_product<T, N, false>(Sz, y, x);
-#pragma unroll
-        for (int k = 0; k < N; ++k) cube[hi * PA + lo * PB + k] = x[k];
-    }
-    __syncthreads();
-    // backward, axis 1
-    if (on) {
-#pragma unroll
-        for (int m = 0; m < N; ++m) x[m] = cube[hi * PA + m * PB + lo];
-        mode_product<T, N, false>(Sy, x, y);
-#pragma unroll
-        for (int j = 0; j < N; ++j) cube[hi * PA + j * PB + lo] = y[j];
-    }
-    __syncthreads();
-    // backward, axis 0
-    if (on) {
-#pragma unroll
-        for (int l = 0; l < N; ++l) x[l] = cube[l * PA + hi * PB + lo];
-        mode_product<T, N, false>(Sx, x, y);
-#pragma unroll
-        for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
-    }
-    __syncthreads();
-
-    // ---- span of v: LDS -> registers -> HBM ------------------------------------------------
-#pragma unroll
-    for (int k = 0; k < ITER; ++k) {
-        const int w = (tid + k * NT) * VEC;
-        if (w < words) {
-            V r;
-            if constexpr (PLAIN) {
-                r = *reinterpret_cast<const V *>(cube_all + w);
-            } else {
-#pragma unroll
-                for (int t = 0; t < VEC; ++t) r[t] = cube_all[lds_index<T, N, G>(w + t)];
-            }
-            if (w + VEC <= words) {
-                gstore<(HINT & 2) != 0>(reinterpret_cast<V *>(v + base + w), r);
-            } else {
-#pragma unroll
-                for (int t = 0; t < VEC; ++t)
-                    if (w + t < words) v[base + w + t] = r[t];
-            }
-        }
-    }
-}
-
 // Per (type, n): elements per workgroup, hint bits, how D_e is brought in, and whether the
 // workgroups are renumbered per accelerator die.  Defaults: the lane-utilisation rule for G,
 // non-temporal stores, D_e loaded straight into its pencil layout (half the LDS), and the

@@ -44,7 +44,7 @@ def lib():
         l.tpo_ihelm_apply.restype = ci
         l.tpo_ihelm_apply_variant.argtypes = [vp, vp, vp, vp, vp, vp, ci, cll, ci, vp, ci]
         l.tpo_ihelm_apply_variant.restype = ci
-        l.tpo_ihelm_variant_for.argtypes = [ci, ci]
+        l.tpo_ihelm_variant_for.argtypes = [ci, ci, ci]
         l.tpo_ihelm_variant_for.restype = ci
         l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_has_variant.restype = ci
@@ -80,8 +80,8 @@ def tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, stream,
                                          int(dtype), stream, int(variant))
 
 
-def tpo_ihelm_variant_for(n: int, dtype: int) -> int:
-    return lib().tpo_ihelm_variant_for(int(n), int(dtype))
+def tpo_ihelm_variant_for(n: int, dtype: int, shared_s: bool = False) -> int:
+    return lib().tpo_ihelm_variant_for(int(n), int(dtype), int(bool(shared_s)))
 
 
 def tpo_ihelm_has_variant(n: int, dtype: int, variant: int) -> bool:

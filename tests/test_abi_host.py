@@ -92,10 +92,12 @@ def test_valid_call_without_create_reports_not_initialized():
 def test_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):
-            var = tpo.tpo_ihelm_variant_for(n, dt)
-            assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA)
-            assert tpo.tpo_ihelm_has_variant(n, dt, var)
+            for shared in (False, True):
+                var = tpo.tpo_ihelm_variant_for(n, dt, shared)
+                assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA)
+                assert tpo.tpo_ihelm_has_variant(n, dt, var)
             assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
+            assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_AUTO)
     assert tpo.tpo_ihelm_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
     assert tpo.tpo_ihelm_variant_for(0, tpo.TPO_F64) == tpo.TPO_ERR_INVALID_ARG
     assert tpo.tpo_ihelm_variant_for(4, 5) == tpo.TPO_ERR_INVALID_ARG

@@ -48,6 +48,10 @@ def test_all_n_small_batches(n, dtype):
             w = wl.custom(n, e, dtype, key=200 + n, distinct_s=True)
             print(f"case n={n} {dtype} E={e} variant={name}", flush=True)
             check_against_oracle(w, name)
+        # one matrix shared by the three directions (same pointer): its own kernel instantiation
+        w = wl.custom(n, 131, dtype, key=250 + n, distinct_s=False)
+        print(f"case n={n} {dtype} E=131 shared S variant={name}", flush=True)
+        check_against_oracle(w, name)
 
 
 def test_config0_all_elements():
