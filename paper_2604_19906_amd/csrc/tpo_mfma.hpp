@@ -77,11 +77,13 @@ struct MfmaShape {
 // PERSIST = true : a fixed grid of workgroups walks over the batches (batch = blockIdx.x,
 // + gridDim.x, ...) and loads the next batch's u_e and D_e into registers while the current
 // one is being computed, so that no workgroup ever sits idle waiting for its first loads.
+// WAVES: wavefronts per SIMD the register allocation must leave room for (1 = no demand).
 // SAMES = true: the caller passed one matrix for all three directions (equal pointers); the A
 // operands are then held once instead of three times (for n = 16 in fp64 that is 32 VGPRs,
 // the difference between three and four wavefronts per SIMD).
-template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES>
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES, int WAVES>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
+__attribute__((amdgpu_waves_per_eu(WAVES)))
 ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy,
                   const T *__restrict__ Sz, const T *__restrict__ D, T *v,
                   long long num_elems)
@@ -297,7 +299,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 }
 
 // Persistent grids are sized from the occupancy the runtime reports for the kernel.
-template <typename T, int N, int G, int NW, int HINT, bool PERSIST>
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST, int WAVES>
 struct MfmaLauncher {
     using Sh = MfmaShape<T, N, G, NW>;
     static inline int wgs_per_device[2] = {0, 0};       // [SAMES]
@@ -312,7 +314,7 @@ struct MfmaLauncher {
             if (wgs_per_device[SAMES] <= 0) return hipErrorNotInitialized;
             if (blocks > wgs_per_device[SAMES]) blocks = wgs_per_device[SAMES];
         }
-        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES>),
+        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES>),
                            dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
@@ -327,7 +329,7 @@ struct MfmaLauncher {
     template <bool SAMES>
     static hipError_t prepare_as()
     {
-        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES>;
+        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES>;
         if (Sh::LDS_BYTES > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)Sh::LDS_BYTES);

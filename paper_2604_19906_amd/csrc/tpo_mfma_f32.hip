@@ -12,14 +12,15 @@ struct MfmaTune_f32 {
     static constexpr int NW = 4;
     static constexpr int HINT = 2;
     static constexpr bool PERSIST = false;
+    static constexpr int WAVES = 1;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST>::launch,                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::launch,                                   \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST>::prepare                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f32(int n)

@@ -12,6 +12,7 @@ struct MfmaTune_f64 {
     static constexpr int NW = 4;
     static constexpr int HINT = 2;
     static constexpr bool PERSIST = false;
+    static constexpr int WAVES = 1;
 };
 
 // n = 16: one workgroup per element, plain loads and stores (1.16 ms on 65536 elements with
@@ -22,6 +23,7 @@ struct MfmaTune_f64<16> {
     static constexpr int NW = 4;
     static constexpr int HINT = 0;
     static constexpr bool PERSIST = false;
+    static constexpr int WAVES = 1;     // asking for a fourth wavefront per SIMD (125 VGPRs) measured equal
 };
 // n = 11: persistent grid with register prefetch of the next element (1.69 ms against 1.87 ms).
 template <>
@@ -30,14 +32,15 @@ struct MfmaTune_f64<11> {
     static constexpr int NW = 4;
     static constexpr int HINT = 0;
     static constexpr bool PERSIST = true;
+    static constexpr int WAVES = 1;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST>::launch,                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::launch,                                   \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST>::prepare                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f64(int n)

@@ -289,22 +289,29 @@ struct PencilTune {
     static constexpr int HINT = 2;
     static constexpr bool DDIRECT = true;
     static constexpr bool XCD = (N * N * N * sizeof(T)) % 128 != 0;
+    static constexpr size_t LDS_MIN = 0;    // LDS requested at least (caps workgroups per CU)
 };
 template <> struct PencilTune<double, 8> {
     static constexpr int G = 4, HINT = 3;
     static constexpr bool DDIRECT = false, XCD = false;
+    static constexpr size_t LDS_MIN = 0;
 };
+// n = 11: asking for 18 KB of LDS (10.4 KB are used) holds the CU at 8 workgroups instead of
+// 12; with fewer loads in flight the memory system runs 1.5 % faster (1.437 against 1.463 ms).
 template <> struct PencilTune<double, 11> {
     static constexpr int G = 1, HINT = 0;
     static constexpr bool DDIRECT = true, XCD = true;
+    static constexpr size_t LDS_MIN = 18 * 1024;
 };
 template <> struct PencilTune<double, 16> {
     static constexpr int G = 1, HINT = 2;
     static constexpr bool DDIRECT = true, XCD = false;
+    static constexpr size_t LDS_MIN = 0;
 };
 template <> struct PencilTune<float, 13> {
     static constexpr int G = 3, HINT = 0;
     static constexpr bool DDIRECT = true, XCD = false;
+    static constexpr size_t LDS_MIN = 0;
 };
 
 template <typename T, int N>
@@ -312,7 +319,8 @@ struct PencilLauncher {
     using Tune = PencilTune<T, N>;
     static constexpr int G = Tune::G;
     using Sh = PencilShape<T, N, G>;
-    static constexpr size_t LDS = Tune::DDIRECT ? Sh::LDS_BYTES / 2 : Sh::LDS_BYTES;
+    static constexpr size_t LDS_USED = Tune::DDIRECT ? Sh::LDS_BYTES / 2 : Sh::LDS_BYTES;
+    static constexpr size_t LDS = LDS_USED > Tune::LDS_MIN ? LDS_USED : Tune::LDS_MIN;
 
     static constexpr auto kernel()
     {
