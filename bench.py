@@ -67,7 +67,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
-    ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma", "pencil_mm"])
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=131072)
@@ -96,10 +96,12 @@ def main() -> int:
         w = wl.Workload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems,
                         w.u_dist, w.distinct_s)
     variant = {"auto": tpo.TPO_VARIANT_AUTO, "pencil": tpo.TPO_VARIANT_PENCIL,
-               "mfma": tpo.TPO_VARIANT_MFMA}[args.variant]
+               "mfma": tpo.TPO_VARIANT_MFMA,
+               "pencil_mm": tpo.TPO_VARIANT_PENCIL_MM}[args.variant]
     dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
     chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt, not w.distinct_s)
-    chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma"}[chosen]
+    chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma",
+                   tpo.TPO_VARIANT_PENCIL_MM: "pencil_mm"}[chosen]
 
     # ---- inputs: seeded, generated block by block on the host, resident in HBM -------------
     t0 = time.time()

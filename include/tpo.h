@@ -41,7 +41,10 @@ typedef enum {
 typedef enum {
     TPO_VARIANT_AUTO = 0,    /* the library's measured choice for (n, dtype) */
     TPO_VARIANT_PENCIL = 1,  /* register-blocked vector FMAs, one pencil per lane */
-    TPO_VARIANT_MFMA = 2     /* matrix-core tiles (v_mfma_f64_16x16x4 / v_mfma_f32_16x16x4) */
+    TPO_VARIANT_MFMA = 2,    /* matrix-core tiles (v_mfma_f64_16x16x4 / v_mfma_f32_16x16x4) */
+    TPO_VARIANT_PENCIL_MM = 3 /* fp32 only: the pencil kernel's data movement, its FMAs issued four
+                                 at a time as 4x4x1 matrix-core outer products
+                                 (v_mfma_f32_4x4x1 with A broadcast) */
 } tpo_variant_t;
 
 #define TPO_MAX_N 16         /* points per direction supported: 1 .. TPO_MAX_N */
@@ -105,7 +108,8 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
  * shared_s != 0 asks about calls that pass ONE matrix for all three directions (S_x, S_y and
  * S_z are the same pointer), 0 about calls with distinct pointers; the choice can differ
  * because the matrix-core kernels hold a shared matrix once.
- * Returns TPO_VARIANT_PENCIL or TPO_VARIANT_MFMA, or TPO_ERR_UNSUPPORTED / TPO_ERR_INVALID_ARG.
+ * Returns TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA or TPO_VARIANT_PENCIL_MM, or TPO_ERR_UNSUPPORTED /
+ * TPO_ERR_INVALID_ARG.
  * Pure host function; needs no device. */
 int tpo_ihelm_variant_for(int n, int dtype, int shared_s);
 

@@ -22,6 +22,11 @@ int auto_variant(int n, int dtype, bool shared_s)
     // fp64 n=16: pencil 1.19; MFMA 1.16 when one matrix is shared by the three directions
     // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
     if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
+    // fp32: with 4x4x1 matrix-core products the pencil kernel leaves the vector-FMA bound
+    // (n=13, E=1048576: 5.5 against 6.0 ms).  Measured over 2 GiB fields for every n: faster
+    // for n = 9, 10 and 12..16 (2 to 18 %), equal within 1 % for n = 4..8 and 11, slower for
+    // n = 2, 3.
+    if (dtype == TPO_F32 && n >= 9 && n != 11) return TPO_VARIANT_PENCIL_MM;
     return TPO_VARIANT_PENCIL;
 }
 
@@ -29,6 +34,7 @@ const tpo::KernelEntry *lookup(int n, int dtype, int variant)
 {
     if (variant == TPO_VARIANT_PENCIL) return tpo::pencil_entry(n, dtype);
     if (variant == TPO_VARIANT_MFMA) return tpo::mfma_entry(n, dtype);
+    if (variant == TPO_VARIANT_PENCIL_MM) return tpo::pencil_mm_entry(n, dtype);
     return nullptr;
 }
 
@@ -53,7 +59,7 @@ int tpo_create(void)
     if (g_refs[dev] == 0) {
         for (int dt = 0; dt < 2; ++dt)
             for (int n = 1; n <= TPO_MAX_N; ++n)
-                for (int var : {TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA}) {
+                for (int var : {TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA, TPO_VARIANT_PENCIL_MM}) {
                     const tpo::KernelEntry *k = lookup(n, dt, var);
                     if (k && k->prepare && k->prepare() != hipSuccess) {
                         (void)hipGetLastError();

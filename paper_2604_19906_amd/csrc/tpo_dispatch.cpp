@@ -7,6 +7,7 @@ const KernelEntry *pencil_entry_f64(int n);
 const KernelEntry *pencil_entry_f32(int n);
 const KernelEntry *mfma_entry_f64(int n);
 const KernelEntry *mfma_entry_f32(int n);
+const KernelEntry *pencil_mm_entry_f32(int n);
 
 const KernelEntry *pencil_entry(int n, int dtype)
 {
@@ -16,6 +17,11 @@ const KernelEntry *pencil_entry(int n, int dtype)
 const KernelEntry *mfma_entry(int n, int dtype)
 {
     return dtype == TPO_F64 ? mfma_entry_f64(n) : mfma_entry_f32(n);
+}
+
+const KernelEntry *pencil_mm_entry(int n, int dtype)
+{
+    return dtype == TPO_F32 ? pencil_mm_entry_f32(n) : nullptr;
 }
 
 }  // namespace tpo

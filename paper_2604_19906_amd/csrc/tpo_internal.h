@@ -24,6 +24,7 @@ struct KernelEntry {
 // no kernel for that shape.
 const KernelEntry *pencil_entry(int n, int dtype);
 const KernelEntry *mfma_entry(int n, int dtype);
+const KernelEntry *pencil_mm_entry(int n, int dtype);   // fp32 only
 
 // Pure host validation shared by the entry points; touches no HIP state.
 int validate_apply(const void *u, const void *sx, const void *sy, const void *sz,

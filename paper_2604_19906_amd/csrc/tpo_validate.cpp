@@ -20,7 +20,7 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
     if (variant != TPO_VARIANT_AUTO && variant != TPO_VARIANT_PENCIL &&
-        variant != TPO_VARIANT_MFMA)
+        variant != TPO_VARIANT_MFMA && variant != TPO_VARIANT_PENCIL_MM)
         return TPO_ERR_INVALID_ARG;
     if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;

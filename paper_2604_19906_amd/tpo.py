@@ -14,7 +14,7 @@ TPO_F64, TPO_F32 = 0, 1
 TPO_OK = 0
 TPO_ERR_INVALID_ARG, TPO_ERR_UNSUPPORTED, TPO_ERR_NOT_INITIALIZED = -1, -2, -3
 TPO_ERR_DEVICE, TPO_ERR_ALIAS = -4, -5
-TPO_VARIANT_AUTO, TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA = 0, 1, 2
+TPO_VARIANT_AUTO, TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA, TPO_VARIANT_PENCIL_MM = 0, 1, 2, 3
 TPO_MAX_N = 16
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtpo.so")

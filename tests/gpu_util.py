@@ -7,7 +7,8 @@ from paper_2604_19906_amd import tpo
 from paper_2604_19906_amd import workloads as wl
 
 TOL = {"f64": 1e-12, "f32": 2e-5}      # max-norm relative error per element
-VARIANTS = {"pencil": tpo.TPO_VARIANT_PENCIL, "mfma": tpo.TPO_VARIANT_MFMA}
+VARIANTS = {"pencil": tpo.TPO_VARIANT_PENCIL, "mfma": tpo.TPO_VARIANT_MFMA,
+            "pencil_mm": tpo.TPO_VARIANT_PENCIL_MM}
 
 
 def dev(a):

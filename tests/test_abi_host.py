@@ -94,10 +94,13 @@ def test_variant_queries():
         for n in range(1, tpo.TPO_MAX_N + 1):
             for shared in (False, True):
                 var = tpo.tpo_ihelm_variant_for(n, dt, shared)
-                assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA)
+                assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA,
+                               tpo.TPO_VARIANT_PENCIL_MM)
                 assert tpo.tpo_ihelm_has_variant(n, dt, var)
             assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
             assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_AUTO)
+            # the 4x4x1 matrix-core pencil kernels exist for fp32 only
+            assert tpo.tpo_ihelm_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL_MM) == (dt == tpo.TPO_F32)
     assert tpo.tpo_ihelm_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
     assert tpo.tpo_ihelm_variant_for(0, tpo.TPO_F64) == tpo.TPO_ERR_INVALID_ARG
     assert tpo.tpo_ihelm_variant_for(4, 5) == tpo.TPO_ERR_INVALID_ARG
