@@ -51,6 +51,9 @@ def _load():
         lib.tpo_oracle_forward_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int,
                                                   ctypes.c_longlong]
         lib.tpo_oracle_forward_lifted.restype = ctypes.c_int
+        lib.tpo_oracle_ihelm_sep.argtypes = [dp] * 9 + [ctypes.c_int, ctypes.c_longlong,
+                                                        ctypes.c_int]
+        lib.tpo_oracle_ihelm_sep.restype = ctypes.c_int
         lib.tpo_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -102,6 +105,27 @@ def ihelm_apply_direct(u, s_x, s_y, s_z, d) -> np.ndarray:
                                          _ptr(v), n, u.shape[0])
     if rc != 0:
         raise RuntimeError(f"tpo_oracle_ihelm_direct failed ({rc})")
+    return v
+
+
+def ihelm_apply_sep(u, s_x, s_y, s_z, lam_x, lam_y, lam_z, mu, nthreads: int = 0) -> np.ndarray:
+    """The operator with the separable diagonal
+    ``D[e,i,j,k] = 1 / (lam_x[i] + lam_y[j] + lam_z[k] + mu[e])`` (fp64, denominator summed left
+    to right).  ``lam_*`` are ``[n]``, ``mu`` is ``[E]``.  Returns fp64 ``[E,n,n,n]``."""
+    u, s_x, s_y, s_z, lam_x, lam_y, lam_z, mu = map(_f64, (u, s_x, s_y, s_z, lam_x, lam_y,
+                                                            lam_z, mu))
+    n = _check_shapes(u, s_x, s_y, s_z, None)
+    for name, lam in (("lam_x", lam_x), ("lam_y", lam_y), ("lam_z", lam_z)):
+        if lam.shape != (n,):
+            raise ValueError(f"{name} must be [{n}], got {lam.shape}")
+    if mu.shape != (u.shape[0],):
+        raise ValueError(f"mu must be [{u.shape[0]}], got {mu.shape}")
+    v = np.empty_like(u)
+    rc = _load().tpo_oracle_ihelm_sep(_ptr(u), _ptr(s_x), _ptr(s_y), _ptr(s_z), _ptr(lam_x),
+                                      _ptr(lam_y), _ptr(lam_z), _ptr(mu), _ptr(v), n,
+                                      u.shape[0], nthreads)
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_ihelm_sep failed ({rc})")
     return v
 
 

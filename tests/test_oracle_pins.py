@@ -223,6 +223,78 @@ def test_workload_diagonal_matches_helmholtz_recipe():
     assert d.min() > 1 / 31.0 and d.max() < 1 / 0.3
 
 
+# --- p9: separable-diagonal form --------------------------------------------------------------
+def helmholtz_matrix(s, lam, mu):
+    """Dense (A_x (x) I (x) I + I (x) A_y (x) I + I (x) I (x) A_z + mu I), A_d = S_d diag(lam_d) S_d^T."""
+    n = s[0].shape[0]
+    k = [s[a] @ np.diag(lam[a]) @ s[a].T for a in range(3)]
+    eye = np.eye(n)
+    return (np.kron(np.kron(k[0], eye), eye) + np.kron(np.kron(eye, k[1]), eye)
+            + np.kron(np.kron(eye, eye), k[2]) + mu * np.eye(n ** 3))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5])
+def test_sep_dense_helmholtz_solve(n):
+    # three different operators, different eigenvalues per direction, a different shift per
+    # element: a swapped lam_x/lam_z, a missing mu or mu indexed by the wrong element fails
+    rng = np.random.default_rng(8100 + n)
+    s = [wl.orthogonal_matrix(n, rng) for _ in range(3)]
+    lam = [rng.uniform(0.1, 10, n) for _ in range(3)]
+    mu = rng.uniform(0, 1, 3)
+    u = rng.uniform(-1, 1, (3, n, n, n))
+    v = oracle.ihelm_apply_sep(u, s[0], s[1], s[2], lam[0], lam[1], lam[2], mu)
+    for e in range(3):
+        ref = np.linalg.solve(helmholtz_matrix(s, lam, mu[e]), u[e].ravel()).reshape(n, n, n)
+        assert np.allclose(v[e], ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+
+
+def test_sep_is_the_d_form_with_the_definition_of_d():
+    # entry by entry: D[e,i,j,k] = 1 / (lam_x[i] + lam_y[j] + lam_z[k] + mu[e]), built here with
+    # explicit loops, given to the D form; 1100 elements cross the oracle's block of 1024
+    n, e = 3, 1100
+    rng = np.random.default_rng(8200)
+    s = [rng.standard_normal((n, n)) for _ in range(3)]
+    lam = [rng.uniform(0.1, 10, n) for _ in range(3)]
+    mu = rng.uniform(0, 1, e)
+    u = rng.uniform(-1, 1, (e, n, n, n))
+    d = np.empty((e, n, n, n))
+    for ee in range(e):
+        for i, j, k in product(range(n), repeat=3):
+            d[ee, i, j, k] = 1.0 / (lam[0][i] + lam[1][j] + lam[2][k] + mu[ee])
+    got = oracle.ihelm_apply_sep(u, s[0], s[1], s[2], lam[0], lam[1], lam[2], mu)
+    ref = oracle.ihelm_apply(u, s[0], s[1], s[2], d)
+    assert np.array_equal(got, ref)
+
+
+def test_sep_planted_mistakes():
+    n = 4
+    rng = np.random.default_rng(8300)
+    s = [wl.orthogonal_matrix(n, rng) for _ in range(3)]
+    lam = [rng.uniform(0.1, 10, n) for _ in range(3)]
+    mu = rng.uniform(0, 1, 2)
+    u = rng.uniform(-1, 1, (2, n, n, n))
+    ref = np.stack([np.linalg.solve(helmholtz_matrix(s, lam, mu[e]), u[e].ravel()).reshape(n, n, n)
+                    for e in range(2)])
+    err = lambda got: oracle.max_rel_err_per_element(got, ref)
+    assert err(oracle.ihelm_apply_sep(u, *s, *lam, mu)) < 1e-12
+    assert err(oracle.ihelm_apply_sep(u, *s, lam[2], lam[1], lam[0], mu)) > 1e-3   # lam_x <-> lam_z
+    assert err(oracle.ihelm_apply_sep(u, *s, *lam, mu[::-1])) > 1e-4               # wrong element's mu
+    assert err(oracle.ihelm_apply_sep(u, *s, *lam, np.zeros(2))) > 1e-4            # dropped mu
+
+
+def test_sep_argument_checks():
+    n = 3
+    rng = np.random.default_rng(8400)
+    s = rng.standard_normal((n, n))
+    lam = rng.uniform(1, 2, n)
+    u = rng.uniform(-1, 1, (2, n, n, n))
+    with pytest.raises(ValueError):
+        oracle.ihelm_apply_sep(u, s, s, s, lam[:2], lam, lam, np.zeros(2))
+    with pytest.raises(ValueError):
+        oracle.ihelm_apply_sep(u, s, s, s, lam, lam, lam, np.zeros(3))
+    assert oracle.ihelm_apply_sep(u[:0], s, s, s, lam, lam, lam, np.zeros(0)).shape == (0, n, n, n)
+
+
 # --- planted mistakes are caught -------------------------------------------------------------
 def test_pins_detect_planted_mistakes():
     n = 4
