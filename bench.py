@@ -68,6 +68,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
     ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma", "pencil_mm"])
+    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep"],
+                    help="ihelm: D read from HBM (the headline); ihelm_sep: D evaluated in the "
+                         "kernel from lam_x, lam_y, lam_z, mu (two HBM streams instead of three)")
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=131072)
@@ -99,7 +102,11 @@ def main() -> int:
                "mfma": tpo.TPO_VARIANT_MFMA,
                "pencil_mm": tpo.TPO_VARIANT_PENCIL_MM}[args.variant]
     dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
-    chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt, not w.distinct_s)
+    sep = args.op == "ihelm_sep"
+    if sep:
+        chosen = variant or tpo.tpo_ihelm_sep_variant_for(w.n, dt)
+    else:
+        chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt, not w.distinct_s)
     chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma",
                    tpo.TPO_VARIANT_PENCIL_MM: "pencil_mm"}[chosen]
 
@@ -107,18 +114,26 @@ def main() -> int:
     t0 = time.time()
     tu, tsx, tsy, tsz, td = wl.to_device(w)
     tv = torch.empty_like(tu)
+    tlam = [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in wl.sep_inputs(w)]
     torch.cuda.synchronize()
-    log(f"[bench] {w.name}: inputs resident after {time.time() - t0:.1f}s "
+    nfields = 2 if sep else 3
+    log(f"[bench] {w.name} ({args.op}): inputs resident after {time.time() - t0:.1f}s "
         f"({3 * tu.numel() * tu.element_size() / 1e9:.2f} GB for u, D, v); variant {chosen_name}")
 
     stream = torch.cuda.current_stream()
     ptrs = (tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(), td.data_ptr(),
             tv.data_ptr())
+    sep_ptrs = ptrs[:4] + tuple(t.data_ptr() for t in tlam) + (tv.data_ptr(),)
 
     def step():
-        rc = tpo.tpo_ihelm_apply_variant(*ptrs, w.n, w.num_elems, dt, stream.cuda_stream, variant)
+        if sep:
+            rc = tpo.tpo_ihelm_apply_sep_variant(*sep_ptrs, w.n, w.num_elems, dt,
+                                                 stream.cuda_stream, variant)
+        else:
+            rc = tpo.tpo_ihelm_apply_variant(*ptrs, w.n, w.num_elems, dt, stream.cuda_stream,
+                                             variant)
         if rc != tpo.TPO_OK:
-            raise tpo.TpoError(rc, "tpo_ihelm_apply")
+            raise tpo.TpoError(rc, "tpo_" + args.op + "_apply")
 
     for _ in range(args.warmup):
         step()
@@ -140,8 +155,10 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
 
     elems_per_s = w.num_elems / (ms_per_step * 1e-3)
-    alg_bytes = w.bytes_per_elem * w.num_elems
-    alg_flop = w.flop_per_elem * w.num_elems
+    # algorithmic traffic: u and v, plus D when it is an input; the separable form adds
+    # 3 adds and a division per point to the flop count
+    alg_bytes = w.bytes_per_elem * w.num_elems * nfields // 3
+    alg_flop = (w.flop_per_elem + (4 * w.n ** 3 if sep else 0)) * w.num_elems
     achieved_gbs = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
     achieved_tflops = alg_flop / (avg_kernel_ms * 1e-3) / 1e12
     log(f"[bench] kernel avg {avg_kernel_ms:.4f} ms (min {min(kernel_ms):.4f}, max "
@@ -163,7 +180,7 @@ def main() -> int:
     b.record(stream)
     torch.cuda.synchronize()
     stream_ms = a.elapsed_time(b) / 10
-    stream_gbs = alg_bytes / (stream_ms * 1e-3) / 1e9
+    stream_gbs = w.bytes_per_elem * w.num_elems / (stream_ms * 1e-3) / 1e9
     log(f"[bench] streaming ceiling v=u.*D: {stream_ms:.4f} ms = {stream_gbs:.0f} GB/s")
 
     # ---- sanity: the timed output is the operator's (oracle on a few elements) --------------
@@ -172,7 +189,10 @@ def main() -> int:
     torch.cuda.synchronize()
     sx, sy, sz = wl.direction_matrices(w)
     lo, hi = 0, min(64, w.num_elems)
-    ref = oracle.ihelm_apply(wl.field_u(w, lo, hi), sx, sy, sz, wl.diagonal_d(w, lo, hi))
+    if sep:
+        ref = oracle.ihelm_apply_sep(wl.field_u(w, lo, hi), sx, sy, sz, *wl.sep_inputs(w, lo, hi))
+    else:
+        ref = oracle.ihelm_apply(wl.field_u(w, lo, hi), sx, sy, sz, wl.diagonal_d(w, lo, hi))
     err = oracle.max_rel_err_per_element(tv[lo:hi].cpu().numpy(), ref)
     tol = 1e-12 if w.dtype == "f64" else 2e-5
     if not err <= tol:
@@ -183,11 +203,18 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         ns = min(args.cpu_sample, w.num_elems)
-        hu, hd = wl.field_u(w, 0, ns), wl.diagonal_d(w, 0, ns)
+        hu = wl.field_u(w, 0, ns)
         cores = oracle.max_threads()
-        oracle.ihelm_apply(hu[:256], sx, sy, sz, hd[:256])          # load + warm
-        t1 = time.perf_counter()
-        oracle.ihelm_apply(hu, sx, sy, sz, hd)
+        if sep:
+            hl = wl.sep_inputs(w, 0, ns)
+            oracle.ihelm_apply_sep(hu[:256], sx, sy, sz, *hl[:3], hl[3][:256])   # load + warm
+            t1 = time.perf_counter()
+            oracle.ihelm_apply_sep(hu, sx, sy, sz, *hl)
+        else:
+            hd = wl.diagonal_d(w, 0, ns)
+            oracle.ihelm_apply(hu[:256], sx, sy, sz, hd[:256])          # load + warm
+            t1 = time.perf_counter()
+            oracle.ihelm_apply(hu, sx, sy, sz, hd)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": ns / cpu_s, "unit": "elements/s", "cores": cores, "kind": "oracle",
                "sample": f"first {ns} elements of {w.name}, one pass, all host threads "
@@ -208,7 +235,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": w.name, "n": w.n, "num_elems": w.num_elems,
+        "config": {"workload": w.name, "op": args.op, "n": w.n, "num_elems": w.num_elems,
                    "variant": chosen_name, "layout": "[E,n,n,n] element-contiguous",
                    "parallelism": "1 GPU"},
         "gflops": alg_flop / (ms_per_step * 1e-3) / 1e9,
@@ -219,7 +246,7 @@ def main() -> int:
         "parity_max_rel_err_sample": err,
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                     "traffic": stored_traffic(w.name, chosen_name)},
+                     "traffic": stored_traffic(w.name + (":sep" if sep else ""), chosen_name)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

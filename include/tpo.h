@@ -118,6 +118,45 @@ int tpo_ihelm_variant_for(int n, int dtype, int shared_s);
 int tpo_ihelm_has_variant(int n, int dtype, int variant);
 
 /*
+ * tpo_ihelm_apply_sep -- the same operator for diagonals of separable (fast-diagonalisation)
+ * form, which is how the evaluated workloads build D_e:
+ *
+ *     D_e[i,j,k] = 1 / (lam_x[i] + lam_y[j] + lam_z[k] + mu[e])
+ *
+ * The kernel evaluates D_e where it is used instead of reading it: one of the three HBM streams
+ * of tpo_ihelm_apply disappears (2*n^3 instead of 3*n^3 words per element), at the price of n^3
+ * divisions per element.  This is the operator's share of the buffer sharing that the paper
+ * credits for part of inv_helm's speed (Sec. 6.2): an array that can be recomputed from 3n + 1
+ * numbers is not materialised.
+ *
+ *   lam_x, lam_y, lam_z   DEVICE pointers, read only, [n] each (may be equal); lam_x pairs with
+ *                         cube axis 0, like S_x
+ *   mu                    DEVICE pointer, read only, [num_elems]
+ *   every other argument  as in tpo_ihelm_apply
+ *
+ * Arithmetic: the denominator is summed left to right, ((lam_x[i] + lam_y[j]) + lam_z[k]) + mu[e],
+ * in `dtype`; its reciprocal is the hardware reciprocal, in fp64 refined by two Newton steps:
+ * within 2 ulp (fp64) / 1 ulp (fp32) of the IEEE quotient for normal denominators, so the result
+ * agrees with tpo_ihelm_apply on an IEEE-divided D_e to a few ulp, not bit for bit.  A zero
+ * denominator gives Inf/NaN; it is not checked.
+ * Errors: as tpo_ihelm_apply (v must not overlap lam_* or mu either); TPO_ERR_UNSUPPORTED
+ * from the _variant form when the family has no separable form for (n, dtype) (the matrix-core
+ * tile kernels have none).
+ */
+int tpo_ihelm_apply_sep(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                        const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
+                        void *v, int n, long long num_elems, int dtype, void *stream);
+
+/* The same with the kernel family forced, and the two queries that go with it (which family
+ * TPO_VARIANT_AUTO selects; whether a family has a separable form for (n, dtype)). */
+int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                                const void *lam_x, const void *lam_y, const void *lam_z,
+                                const void *mu, void *v, int n, long long num_elems, int dtype,
+                                void *stream, int variant);
+int tpo_ihelm_sep_variant_for(int n, int dtype);
+int tpo_ihelm_sep_has_variant(int n, int dtype, int variant);
+
+/*
  * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming
  * kernel v[i] = u[i] * D[i], i < count, over flat DEVICE arrays of `dtype`.  It moves the
  * operator's algorithmic traffic (two reads and one write per word) and nothing else, so the

@@ -131,6 +131,66 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
     return TPO_OK;
 }
 
+int tpo_ihelm_sep_variant_for(int n, int dtype)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (n < 1) return TPO_ERR_INVALID_ARG;
+    if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    // The matrix-core tile kernels have no separable-diagonal form; otherwise as for the D form.
+    int var = auto_variant(n, dtype, false);
+    const tpo::KernelEntry *k = lookup(n, dtype, var);
+    if (!k || !k->launch_sep) var = TPO_VARIANT_PENCIL;
+    return var;
+}
+
+int tpo_ihelm_sep_has_variant(int n, int dtype, int variant)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return 0;
+    if (n < 1 || n > TPO_MAX_N) return 0;
+    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_sep_variant_for(n, dtype);
+    const tpo::KernelEntry *k = lookup(n, dtype, variant);
+    return k != nullptr && k->launch_sep != nullptr;
+}
+
+int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                                const void *lam_x, const void *lam_y, const void *lam_z,
+                                const void *mu, void *v, int n, long long num_elems, int dtype,
+                                void *stream, int variant)
+{
+    const int rc = tpo::validate_apply_sep(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n,
+                                           num_elems, dtype, variant);
+    if (rc != TPO_OK) return rc;
+    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_sep_variant_for(n, dtype);
+    const tpo::KernelEntry *k = lookup(n, dtype, variant);
+    if (!k || !k->launch_sep) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_NOT_INITIALIZED;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
+    }
+    tpo::ApplyArgs a{u, S_x, S_y, S_z, nullptr, v, num_elems, (hipStream_t)stream,
+                     lam_x, lam_y, lam_z, mu};
+    if (k->launch_sep(a) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    return TPO_OK;
+}
+
+int tpo_ihelm_apply_sep(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                        const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
+                        void *v, int n, long long num_elems, int dtype, void *stream)
+{
+    return tpo_ihelm_apply_sep_variant(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n, num_elems,
+                                       dtype, stream, TPO_VARIANT_AUTO);
+}
+
 int tpo_ihelm_apply(const void *u, const void *S_x, const void *S_y, const void *S_z,
                     const void *D, void *v, int n, long long num_elems, int dtype,
                     void *stream)

@@ -11,12 +11,15 @@ struct ApplyArgs {
     void *v;
     long long num_elems;
     hipStream_t stream;
+    // separable diagonal (tpo_ihelm_apply_sep): d is null and these are set
+    const void *lam_x = nullptr, *lam_y = nullptr, *lam_z = nullptr, *mu = nullptr;
 };
 
 // One kernel instantiation for a fixed (n, dtype): how to launch it and how to prepare it
 // once per device (e.g. raise its dynamic-LDS limit).
 struct KernelEntry {
     hipError_t (*launch)(const ApplyArgs &);
+    hipError_t (*launch_sep)(const ApplyArgs &);   // null: no separable-diagonal form
     hipError_t (*prepare)();
 };
 
@@ -30,5 +33,8 @@ const KernelEntry *pencil_mm_entry(int n, int dtype);   // fp32 only
 int validate_apply(const void *u, const void *sx, const void *sy, const void *sz,
                    const void *d, const void *v, int n, long long num_elems, int dtype,
                    int variant);
+int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,
+                       const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
+                       const void *v, int n, long long num_elems, int dtype, int variant);
 
 }  // namespace tpo

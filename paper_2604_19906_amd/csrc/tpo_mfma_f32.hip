@@ -19,6 +19,7 @@ struct MfmaTune_f32 {
     KernelEntry {                                                                         \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
                       MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::launch,                                   \
+        nullptr,                                                                          \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
                       MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::prepare                                   \
     }

@@ -39,6 +39,7 @@ struct MfmaTune_f64<11> {
     KernelEntry {                                                                         \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
                       MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::launch,                                   \
+        nullptr,                                                                          \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
                       MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::prepare                                   \
     }

@@ -27,6 +27,26 @@ namespace tpo {
 __device__ __forceinline__ double fma_(double a, double b, double c) { return __builtin_fma(a, b, c); }
 __device__ __forceinline__ float fma_(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 
+// 1/x for the separable diagonal.  EXACT: IEEE division.  Otherwise the hardware reciprocal,
+// in fp64 followed by two Newton steps (v_rcp_f64 delivers about single precision): within
+// 2 ulp for normal x, a third of the instructions of the IEEE sequence.
+template <bool EXACT>
+__device__ __forceinline__ double recip_(double x)
+{
+    if constexpr (EXACT) return 1.0 / x;
+    double r = __builtin_amdgcn_rcp(x);
+    double e = __builtin_fma(-x, r, 1.0);
+    r = __builtin_fma(r, e, r);
+    e = __builtin_fma(-x, r, 1.0);
+    return __builtin_fma(r, e, r);
+}
+template <bool EXACT>
+__device__ __forceinline__ float recip_(float x)
+{
+    if constexpr (EXACT) return 1.0f / x;
+    return __builtin_amdgcn_rcpf(x);
+}
+
 template <typename T, int N, int G>
 struct PencilShape {
     static constexpr int P = N * N;                         // pencils per element
@@ -181,10 +201,17 @@ __device__ __forceinline__ long long pencil_batch(long long nbatch)
     }
 }
 
-template <typename T, int N, int G, int HINT, bool DDIRECT = false, bool XCD = false>
+// SEP != 0 : D_e is not read; it is evaluated where it is used from the separable form
+//            D_e[a][b][c] = 1 / (lam_x[a] + lam_y[b] + lam_z[c] + mu[e])
+//            (sum left to right; SEP = 1: IEEE division, SEP = 2: recip_<false>); D is ignored
+//            and may be null.
+template <typename T, int N, int G, int HINT, bool DDIRECT = false, bool XCD = false,
+          int SEP = 0>
 __global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
 ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
-                    const T *__restrict__ D, T *v, long long num_elems)
+                    const T *__restrict__ D, T *v, long long num_elems,
+                    const T *__restrict__ lam_x, const T *__restrict__ lam_y,
+                    const T *lam_z_, const T *__restrict__ mu)
 {
     using Sh = PencilShape<T, N, G>;
     constexpr int P = Sh::P, PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE;
@@ -215,10 +242,14 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
 
     // forward, axis 0: lane (b,c) = (hi,lo); global reads are consecutive over lanes
     T dd[N];
+    T sep_ab = T(0), sep_mu = T(0);     // lam_x[a] + lam_y[b] of the lane's axis-2 pencil, mu[e]
     if (on) {
 #pragma unroll
         for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base + (size_t)(l * P + p));
-        if constexpr (DDIRECT) {
+        if constexpr (SEP != 0) {
+            sep_ab = lam_x[hi] + lam_y[lo];
+            sep_mu = mu[e];
+        } else if constexpr (DDIRECT) {
             load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);   // D_e[a][b][0..n-1]
         } else {
 #pragma unroll
@@ -227,7 +258,7 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
         mode_product<T, N, true>(Sx, x, y);
 #pragma unroll
         for (int i = 0; i < N; ++i) cube[i * PA + hi * PB + lo] = y[i];
-        if constexpr (!DDIRECT) {
+        if constexpr (!DDIRECT && SEP == 0) {
 #pragma unroll
             for (int l = 0; l < N; ++l) dpark[l * PA + hi * PB + lo] = dd[l];
         }
@@ -248,9 +279,14 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     if (on) {
 #pragma unroll
         for (int q = 0; q < N; ++q) x[q] = cube[hi * PA + lo * PB + q];
+        if constexpr (SEP != 0) {
+            const TPO_CONSTANT T *lam_z = (const TPO_CONSTANT T *)lam_z_;
+#pragma unroll
+            for (int k = 0; k < N; ++k) dd[k] = recip_<SEP == 1>((sep_ab + lam_z[k]) + sep_mu);
+        }
         mode_product<T, N, true>(Sz, x, y);
 #pragma unroll
-        for (int k = 0; k < N; ++k) y[k] *= DDIRECT ? dd[k] : dpark[hi * PA + lo * PB + k];
+        for (int k = 0; k < N; ++k) y[k] *= (DDIRECT || SEP != 0) ? dd[k] : dpark[hi * PA + lo * PB + k];
         mode_product<T, N, false>(Sz, y, x);
 #pragma unroll
         for (int k = 0; k < N; ++k) cube[hi * PA + lo * PB + k] = x[k];
@@ -314,17 +350,31 @@ template <> struct PencilTune<float, 13> {
     static constexpr size_t LDS_MIN = 0;
 };
 
+// Tuning of the separable-diagonal form: as the D form unless measured otherwise.  Without the
+// D_e stream a workgroup has half the loads in flight, so the D form's occupancy cap at n = 11
+// and its four elements per workgroup at n = 8 no longer pay (n = 11: 1.27 against 1.35 ms;
+// n = 8: 0.202 against 0.215 ms).
 template <typename T, int N>
-struct PencilLauncher {
-    using Tune = PencilTune<T, N>;
+struct PencilSepTune : PencilTune<T, N> {};
+template <> struct PencilSepTune<double, 11> : PencilTune<double, 11> {
+    static constexpr size_t LDS_MIN = 0;
+};
+template <> struct PencilSepTune<double, 8> : PencilTune<double, 8> {
+    static constexpr int G = 1;
+};
+
+// SEP: 0 = D read from memory, 1 / 2 = separable diagonal (IEEE division / fast reciprocal).
+template <typename T, int N, typename Tune, int SEP>
+struct PencilLauncherT {
     static constexpr int G = Tune::G;
     using Sh = PencilShape<T, N, G>;
-    static constexpr size_t LDS_USED = Tune::DDIRECT ? Sh::LDS_BYTES / 2 : Sh::LDS_BYTES;
+    static constexpr bool DDIRECT = Tune::DDIRECT || SEP != 0;   // no D_e in LDS either way
+    static constexpr size_t LDS_USED = DDIRECT ? Sh::LDS_BYTES / 2 : Sh::LDS_BYTES;
     static constexpr size_t LDS = LDS_USED > Tune::LDS_MIN ? LDS_USED : Tune::LDS_MIN;
 
     static constexpr auto kernel()
     {
-        return &ihelm_pencil_kernel<T, N, G, Tune::HINT, Tune::DDIRECT, Tune::XCD>;
+        return &ihelm_pencil_kernel<T, N, G, Tune::HINT, DDIRECT, Tune::XCD, SEP>;
     }
 
     static hipError_t launch(const ApplyArgs &a)
@@ -333,7 +383,8 @@ struct PencilLauncher {
         if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
-                           (const T *)a.d, (T *)a.v, a.num_elems);
+                           (const T *)a.d, (T *)a.v, a.num_elems, (const T *)a.lam_x,
+                           (const T *)a.lam_y, (const T *)a.lam_z, (const T *)a.mu);
         return hipGetLastError();
     }
 
@@ -345,7 +396,21 @@ struct PencilLauncher {
     }
 };
 
-#define TPO_PENCIL_ENTRY(T, N) \
-    KernelEntry { &PencilLauncher<T, N>::launch, &PencilLauncher<T, N>::prepare }
+template <typename T, int N>
+struct PencilLauncher {
+    using Plain = PencilLauncherT<T, N, PencilTune<T, N>, 0>;
+    using Sep = PencilLauncherT<T, N, PencilSepTune<T, N>, 2>;   // fast reciprocal
+    static hipError_t launch(const ApplyArgs &a) { return Plain::launch(a); }
+    static hipError_t launch_sep(const ApplyArgs &a) { return Sep::launch(a); }
+    static hipError_t prepare()
+    {
+        const hipError_t rc = Plain::prepare();
+        return rc != hipSuccess ? rc : Sep::prepare();
+    }
+};
+
+#define TPO_PENCIL_ENTRY(T, N)                                                        \
+    KernelEntry { &PencilLauncher<T, N>::launch, &PencilLauncher<T, N>::launch_sep, \
+                  &PencilLauncher<T, N>::prepare }
 
 }  // namespace tpo

@@ -144,11 +144,15 @@ __device__ __forceinline__ void mode_product_mm(const float (&tab)[MmShape<N>::N
 // HINT and XCD as in ihelm_pencil_kernel; D_e is always loaded in its pencil layout.
 // The matrix instructions ignore the execution mask, so they run outside the `on` branches
 // on every lane; idle lanes carry zeros or stale LDS words and never store.
-template <int N, int G, int HINT, bool XCD>
+// SEP as in ihelm_pencil_kernel: D_e evaluated from lam_x, lam_y, lam_z, mu instead of read
+// (1: IEEE division, 2: hardware reciprocal, 1 ulp).
+template <int N, int G, int HINT, bool XCD, int SEP = 0>
 __global__ void __launch_bounds__((PencilShape<float, N, G>::NT))
 ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float *__restrict__ Sy,
                        const float *__restrict__ Sz, const float *__restrict__ D, float *v,
-                       long long num_elems)
+                       long long num_elems, const float *__restrict__ lam_x,
+                       const float *__restrict__ lam_y, const float *lam_z_,
+                       const float *__restrict__ mu)
 {
     using Sh = PencilShape<float, N, G>;
     using M = MmShape<N>;
@@ -175,6 +179,7 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
 
     float x[N], y[NY], dd[N];
     float tab[M::NTAB];
+    float sep_ab = 1.0f, sep_mu = 0.0f;   // lam_x[a] + lam_y[b] of the lane's axis-2 pencil, mu[e]
 
     // forward, axis 0: lane (b,c) = (hi,lo)
 #pragma unroll
@@ -182,7 +187,12 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     if (on) {
 #pragma unroll
         for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base + (size_t)(l * P + p));
-        load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);
+        if constexpr (SEP != 0) {
+            sep_ab = lam_x[hi] + lam_y[lo];
+            sep_mu = mu[e];
+        } else {
+            load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);
+        }
     } else {
 #pragma unroll
         for (int l = 0; l < N; ++l) { x[l] = 0.0f; dd[l] = 0.0f; }
@@ -216,6 +226,11 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
 #pragma unroll
     for (int q = 0; q < N; ++q) x[q] = cube[hi * PA + lo * PB + q];
     mode_product_mm<N, true>(tab, (const TPO_CONSTANT float *)Sz, x, y);
+    if constexpr (SEP != 0) {
+        const TPO_CONSTANT float *lam_z = (const TPO_CONSTANT float *)lam_z_;
+#pragma unroll
+        for (int k = 0; k < N; ++k) dd[k] = recip_<SEP == 1>((sep_ab + lam_z[k]) + sep_mu);
+    }
 #pragma unroll
     for (int k = 0; k < N; ++k) x[k] = y[k] * dd[k];
     mm_fetch_table<N>(tabs, 3, lane, tab);
@@ -268,27 +283,40 @@ struct PencilMmLauncher {
     using Sh = PencilShape<float, N, G>;
     static constexpr size_t LDS = Sh::LDS_BYTES / 2 + MmShape<N>::TAB_LDS_BYTES;
 
-    static constexpr auto kernel() { return &ihelm_pencil_mm_kernel<N, G, Tune::HINT, Tune::XCD>; }
+    template <bool SEP>
+    static constexpr auto kernel()
+    {
+        return &ihelm_pencil_mm_kernel<N, G, Tune::HINT, Tune::XCD, SEP ? 2 : 0>;
+    }
 
-    static hipError_t launch(const ApplyArgs &a)
+    template <bool SEP>
+    static hipError_t launch_as(const ApplyArgs &a)
     {
         const long long blocks = pencil_grid<Tune::XCD>((a.num_elems + G - 1) / G);
         if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
+        hipLaunchKernelGGL(kernel<SEP>(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const float *)a.u, (const float *)a.sx, (const float *)a.sy,
-                           (const float *)a.sz, (const float *)a.d, (float *)a.v, a.num_elems);
+                           (const float *)a.sz, (const float *)a.d, (float *)a.v, a.num_elems,
+                           (const float *)a.lam_x, (const float *)a.lam_y,
+                           (const float *)a.lam_z, (const float *)a.mu);
         return hipGetLastError();
     }
+    static hipError_t launch(const ApplyArgs &a) { return launch_as<false>(a); }
+    static hipError_t launch_sep(const ApplyArgs &a) { return launch_as<true>(a); }
 
     static hipError_t prepare()
     {
         if (LDS <= 48 * 1024) return hipSuccess;
-        return hipFuncSetAttribute((const void *)kernel(),
+        hipError_t rc = hipFuncSetAttribute((const void *)kernel<false>(),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        if (rc != hipSuccess) return rc;
+        return hipFuncSetAttribute((const void *)kernel<true>(),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
     }
 };
 
-#define TPO_PENCIL_MM_ENTRY(N) \
-    KernelEntry { &PencilMmLauncher<N>::launch, &PencilMmLauncher<N>::prepare }
+#define TPO_PENCIL_MM_ENTRY(N)                                                  \
+    KernelEntry { &PencilMmLauncher<N>::launch, &PencilMmLauncher<N>::launch_sep, \
+                  &PencilMmLauncher<N>::prepare }
 
 }  // namespace tpo

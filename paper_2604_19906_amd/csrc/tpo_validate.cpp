@@ -42,4 +42,35 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
     return TPO_OK;
 }
 
+int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,
+                       const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
+                       const void *v, int n, long long num_elems, int dtype, int variant)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (variant != TPO_VARIANT_AUTO && variant != TPO_VARIANT_PENCIL &&
+        variant != TPO_VARIANT_MFMA && variant != TPO_VARIANT_PENCIL_MM)
+        return TPO_ERR_INVALID_ARG;
+    if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
+    if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+    if (!u || !sx || !sy || !sz || !lam_x || !lam_y || !lam_z || !mu || !v)
+        return TPO_ERR_INVALID_ARG;
+    const size_t w = (dtype == TPO_F64) ? 8 : 4;
+    const void *ptrs[9] = {u, sx, sy, sz, lam_x, lam_y, lam_z, mu, v};
+    for (const void *p : ptrs)
+        if ((uintptr_t)p % w) return TPO_ERR_INVALID_ARG;
+    if ((unsigned long long)num_elems > (~(size_t)0 >> 16)) return TPO_ERR_INVALID_ARG;
+    const size_t field = (size_t)num_elems * n * n * n * w;
+    const size_t mat = (size_t)n * n * w;
+    const size_t vec = (size_t)n * w;
+    if (v != u && overlaps(v, field, u, field)) return TPO_ERR_ALIAS;
+    if (overlaps(v, field, sx, mat) || overlaps(v, field, sy, mat) ||
+        overlaps(v, field, sz, mat))
+        return TPO_ERR_ALIAS;
+    if (overlaps(v, field, lam_x, vec) || overlaps(v, field, lam_y, vec) ||
+        overlaps(v, field, lam_z, vec) || overlaps(v, field, mu, (size_t)num_elems * w))
+        return TPO_ERR_ALIAS;
+    return TPO_OK;
+}
+
 }  // namespace tpo

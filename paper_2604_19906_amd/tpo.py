@@ -48,6 +48,14 @@ def lib():
         l.tpo_ihelm_variant_for.restype = ci
         l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_has_variant.restype = ci
+        l.tpo_ihelm_apply_sep.argtypes = [vp] * 9 + [ci, cll, ci, vp]
+        l.tpo_ihelm_apply_sep.restype = ci
+        l.tpo_ihelm_apply_sep_variant.argtypes = [vp] * 9 + [ci, cll, ci, vp, ci]
+        l.tpo_ihelm_apply_sep_variant.restype = ci
+        l.tpo_ihelm_sep_variant_for.argtypes = [ci, ci]
+        l.tpo_ihelm_sep_variant_for.restype = ci
+        l.tpo_ihelm_sep_has_variant.argtypes = [ci, ci, ci]
+        l.tpo_ihelm_sep_has_variant.restype = ci
         l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
         l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
@@ -88,6 +96,28 @@ def tpo_ihelm_has_variant(n: int, dtype: int, variant: int) -> bool:
     return bool(lib().tpo_ihelm_has_variant(int(n), int(dtype), int(variant)))
 
 
+def tpo_ihelm_apply_sep(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n, num_elems, dtype,
+                        stream) -> int:
+    """Raw call of the separable-diagonal form: integer device pointers in, status out."""
+    return lib().tpo_ihelm_apply_sep(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, int(n),
+                                     int(num_elems), int(dtype), stream)
+
+
+def tpo_ihelm_apply_sep_variant(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n, num_elems,
+                                dtype, stream, variant) -> int:
+    return lib().tpo_ihelm_apply_sep_variant(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v,
+                                             int(n), int(num_elems), int(dtype), stream,
+                                             int(variant))
+
+
+def tpo_ihelm_sep_variant_for(n: int, dtype: int) -> int:
+    return lib().tpo_ihelm_sep_variant_for(int(n), int(dtype))
+
+
+def tpo_ihelm_sep_has_variant(n: int, dtype: int, variant: int) -> bool:
+    return bool(lib().tpo_ihelm_sep_has_variant(int(n), int(dtype), int(variant)))
+
+
 def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:
     """Measurement aid: v[i] = u[i] * D[i] over flat device arrays (streaming ceiling)."""
     return lib().tpo_stream_scale(u, D, v, int(count), int(dtype), stream)
@@ -124,4 +154,40 @@ def apply_tensors(u, S_x, S_y, S_z, D, v=None, variant: int = TPO_VARIANT_AUTO):
     check(tpo_ihelm_apply_variant(u.data_ptr(), S_x.data_ptr(), S_y.data_ptr(),
                                   S_z.data_ptr(), D.data_ptr(), v.data_ptr(), n, e, dtype,
                                   stream, variant), "tpo_ihelm_apply")
+    return v
+
+
+def apply_sep_tensors(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v=None,
+                      variant: int = TPO_VARIANT_AUTO):
+    """Separable-diagonal form over torch device tensors (``lam_*`` are ``[n]``, ``mu`` is
+    ``[E]``); marshalling only, like :func:`apply_tensors`."""
+    import torch
+
+    if u.dim() != 4 or not u.is_cuda:
+        raise ValueError("u must be a device tensor of shape [E,n,n,n]")
+    for t in (u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu):
+        if not t.is_contiguous() or t.dtype != u.dtype or not t.is_cuda:
+            raise ValueError("all tensors must be contiguous device tensors of one dtype")
+    e, n = u.shape[0], u.shape[1]
+    if tuple(u.shape[1:]) != (n, n, n):
+        raise ValueError("u must be [E,n,n,n]")
+    for s in (S_x, S_y, S_z):
+        if tuple(s.shape) != (n, n):
+            raise ValueError("S matrices must be [n,n]")
+    for lam in (lam_x, lam_y, lam_z):
+        if tuple(lam.shape) != (n,):
+            raise ValueError("lam vectors must be [n]")
+    if tuple(mu.shape) != (e,):
+        raise ValueError("mu must be [E]")
+    if v is None:
+        v = torch.empty_like(u)
+    elif (tuple(v.shape) != tuple(u.shape) or v.dtype != u.dtype or not v.is_contiguous()
+          or not v.is_cuda):
+        raise ValueError("v must match u")
+    dtype = {torch.float64: TPO_F64, torch.float32: TPO_F32}[u.dtype]
+    stream = torch.cuda.current_stream().cuda_stream
+    check(tpo_ihelm_apply_sep_variant(u.data_ptr(), S_x.data_ptr(), S_y.data_ptr(),
+                                      S_z.data_ptr(), lam_x.data_ptr(), lam_y.data_ptr(),
+                                      lam_z.data_ptr(), mu.data_ptr(), v.data_ptr(), n, e,
+                                      dtype, stream, variant), "tpo_ihelm_apply_sep")
     return v

@@ -173,14 +173,27 @@ def diagonal_d(w: Workload, start: int = 0, stop: int | None = None) -> np.ndarr
     return out
 
 
+def sep_inputs(w: Workload, start: int = 0, stop: int | None = None):
+    """``(lam_x, lam_y, lam_z, mu)`` for elements ``start..stop-1`` in the workload's dtype:
+    the numbers the separable-diagonal form takes instead of ``D`` (each rounded once from
+    fp64; a shared eigenvalue vector is returned three times as the same array)."""
+    lx, ly, lz = eigenvalues(w)
+    mu = shifts(w, start, stop).astype(w.np_dtype)
+    if lx is ly and ly is lz:
+        lam = lx.astype(w.np_dtype)
+        return lam, lam, lam, mu
+    return lx.astype(w.np_dtype), ly.astype(w.np_dtype), lz.astype(w.np_dtype), mu
+
+
 def make_inputs(w: Workload, start: int = 0, stop: int | None = None):
     """``(u, S_x, S_y, S_z, D)`` for elements ``start..stop-1`` as host arrays."""
     sx, sy, sz = direction_matrices(w)
     return field_u(w, start, stop), sx, sy, sz, diagonal_d(w, start, stop)
 
 
-def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK):
-    """Device tensors ``(u, S_x, S_y, S_z, D)`` of a whole workload on the current GPU.
+def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK, with_d: bool = True):
+    """Device tensors ``(u, S_x, S_y, S_z, D)`` of a whole workload on the current GPU
+    (``(u, S_x, S_y, S_z)`` with ``with_d=False``, for the separable-diagonal form).
     Fields are generated block by block on the host (each block from its own seed, several
     blocks at a time) and copied into place, so host memory stays small even for fields of
     many gigabytes.  A shared matrix is uploaded once and returned three times."""
@@ -191,20 +204,23 @@ def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK):
     e, n = w.num_elems, w.n
     tdtype = torch.float64 if w.dtype == "f64" else torch.float32
     tu = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")
-    td = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")
+    td = torch.empty((e, n, n, n), dtype=tdtype, device="cuda") if with_d else None
     spans = [(lo, min(e, lo + chunk)) for lo in range(0, e, chunk)]
 
     def gen(span):
         lo, hi = span
-        return lo, hi, field_u(w, lo, hi), diagonal_d(w, lo, hi)
+        return lo, hi, field_u(w, lo, hi), (diagonal_d(w, lo, hi) if with_d else None)
 
     with ThreadPoolExecutor(max_workers=threads) as ex:
         for lo, hi, hu, hd in ex.map(gen, spans):
             tu[lo:hi].copy_(torch.from_numpy(hu))
-            td[lo:hi].copy_(torch.from_numpy(hd))
+            if with_d:
+                td[lo:hi].copy_(torch.from_numpy(hd))
     sx, sy, sz = direction_matrices(w)
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     if sx is sy and sy is sz:
         ts = up(sx)
-        return tu, ts, ts, ts, td
-    return tu, up(sx), up(sy), up(sz), td
+        mats = (ts, ts, ts)
+    else:
+        mats = (up(sx), up(sy), up(sz))
+    return (tu, *mats, td) if with_d else (tu, *mats)

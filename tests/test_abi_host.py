@@ -89,6 +89,52 @@ def test_valid_call_without_create_reports_not_initialized():
     assert tpo.tpo_create() == tpo.TPO_ERR_DEVICE
 
 
+def test_sep_argument_validation():
+    n, e = 4, 10
+    keep, p = [], []
+    for _ in range(9):
+        a, addr = _buf(e * n ** 3 * 8)
+        keep.append(a)
+        p.append(addr)
+    u, sx, sy, sz, lx, ly, lz, mu, v = p
+    ap = tpo.tpo_ihelm_apply_sep
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, v, 0, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, v, n, -1, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, v, n, e, 3, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, v, 17, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    for k in range(9):
+        q = list(p)
+        q[k] = None
+        assert ap(*q, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, lx + 4, ly, lz, mu, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    # aliasing: v may be u exactly, nothing else
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, u + 8, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, lx, ly, lz, v + 8, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, v, ly, lz, mu, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, v + 16, sz, lx, ly, lz, mu, v, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    # valid arguments, E = 0: no-op; E > 0 without a device: not initialised
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, v, n, 0, tpo.TPO_F64, None) == tpo.TPO_OK
+    assert ap(u, sx, sy, sz, lx, ly, lz, mu, u, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_NOT_INITIALIZED
+    assert tpo.tpo_ihelm_apply_sep_variant(u, sx, sy, sz, lx, ly, lz, mu, v, n, e, tpo.TPO_F64,
+                                           None, 9) == tpo.TPO_ERR_INVALID_ARG
+    assert tpo.tpo_ihelm_apply_sep_variant(u, sx, sy, sz, lx, ly, lz, mu, v, n, e, tpo.TPO_F64,
+                                           None, tpo.TPO_VARIANT_MFMA) == tpo.TPO_ERR_UNSUPPORTED
+
+
+def test_sep_variant_queries():
+    for dt in (tpo.TPO_F64, tpo.TPO_F32):
+        for n in range(1, tpo.TPO_MAX_N + 1):
+            var = tpo.tpo_ihelm_sep_variant_for(n, dt)
+            assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_PENCIL_MM)
+            assert tpo.tpo_ihelm_sep_has_variant(n, dt, var)
+            assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_AUTO)
+            assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
+            assert not tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_MFMA)
+            assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL_MM) == (dt == tpo.TPO_F32)
+    assert tpo.tpo_ihelm_sep_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
+    assert tpo.tpo_ihelm_sep_variant_for(0, tpo.TPO_F32) == tpo.TPO_ERR_INVALID_ARG
+
+
 def test_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):

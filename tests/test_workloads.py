@@ -51,3 +51,18 @@ def test_value_ranges():
     w4 = wl.custom(13, 8, "f32", key=4)
     u4, *_rest, d4 = wl.make_inputs(w4)
     assert u4.dtype == np.float32 and d4.dtype == np.float32
+
+
+def test_sep_inputs_match_the_diagonal():
+    # the separable-diagonal inputs are the numbers the D recipe is built from
+    w = wl.custom(5, 9, "f64", key=11, distinct_s=True)
+    lx, ly, lz, mu = wl.sep_inputs(w)
+    d = wl.diagonal_d(w)
+    want = 1.0 / (lx[None, :, None, None] + ly[None, None, :, None] + lz[None, None, None, :]
+                  + mu[:, None, None, None])
+    assert np.array_equal(d, want)
+    lx2, _, _, mu2 = wl.sep_inputs(w, 3, 7)
+    assert np.array_equal(mu2, mu[3:7]) and np.array_equal(lx2, lx)
+    w32 = wl.custom(4, 3, "f32", key=12, distinct_s=False)
+    l32 = wl.sep_inputs(w32)
+    assert all(a.dtype == np.float32 for a in l32) and l32[0] is l32[1]
