@@ -23,10 +23,10 @@ int auto_variant(int n, int dtype, bool shared_s)
     // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
     if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
     // fp32: with 4x4x1 matrix-core products the pencil kernel leaves the vector-FMA bound
-    // (n=13, E=1048576: 5.5 against 6.0 ms).  Measured over 2 GiB fields for every n: faster
-    // for n = 9, 10 and 12..16 (2 to 18 %), equal within 1 % for n = 4..8 and 11, slower for
-    // n = 2, 3.
-    if (dtype == TPO_F32 && n >= 9 && n != 11) return TPO_VARIANT_PENCIL_MM;
+    // (n=13, E=1048576: 5.5 against 6.0 ms).  Sweep over every n on 1 GiB fields, each family
+    // at its best setting: the 4x4x1 kernels win for n >= 9 (2 to 19 %), the vector-FMA ones
+    // for n <= 8 (2 to 8 %).
+    if (dtype == TPO_F32 && n >= 9) return TPO_VARIANT_PENCIL_MM;
     return TPO_VARIANT_PENCIL;
 }
 

@@ -313,24 +313,38 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
     }
 }
 
-// Per (type, n): elements per workgroup, hint bits, how D_e is brought in, and whether the
-// workgroups are renumbered per accelerator die.  Defaults: the lane-utilisation rule for G,
-// non-temporal stores, D_e loaded straight into its pencil layout (half the LDS), and the
-// renumbering whenever an element is not a whole number of 128-byte lines.  The
-// specialisations are the best of sweeps on MI355X at the sizes of the named workloads
-// (G in {1,2,4,8} x hint bits x D mode x renumbering).
+// Per (type, n): elements per workgroup G, hint bits, how D_e is brought in (1: straight into
+// its pencil layout, half the LDS; 0: coalesced and parked in LDS), and whether the workgroups
+// are renumbered per accelerator die.  One row per n = 1..16: the best of a sweep on MI355X over
+// G in {1,2,3,4,6,8,12,16,32} x hint bits x D mode x renumbering on 1 GiB fields; n = 8, 11, 16
+// (fp64) and 13 (fp32) are the sweeps at the sizes of the named workloads.  n = 1 keeps the
+// lane-utilisation rule (G = 0 in the table).
+struct PencilRow { int g, hint, ddirect, xcd; };
+template <typename T> struct PencilTable;
+template <> struct PencilTable<double> {
+    static constexpr PencilRow row[TPO_MAX_N + 1] = {
+        {0, 2, 1, 0},
+        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {4, 3, 0, 0},  {16, 0, 1, 0}, {16, 0, 1, 0},
+        {1, 3, 0, 1},  {4, 3, 0, 0},  {2, 0, 1, 0},  {2, 2, 1, 1},  {1, 0, 1, 1},  {3, 2, 1, 0},
+        {3, 0, 1, 0},  {1, 0, 1, 0},  {1, 0, 1, 0},  {1, 2, 1, 0},
+    };
+};
+template <> struct PencilTable<float> {
+    static constexpr PencilRow row[TPO_MAX_N + 1] = {
+        {0, 2, 1, 0},
+        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 1}, {8, 2, 1, 0},  {16, 0, 1, 0}, {12, 0, 1, 0},
+        {4, 2, 1, 1},  {4, 3, 0, 0},  {3, 0, 1, 0},  {4, 0, 1, 1},  {2, 0, 1, 0},  {3, 2, 1, 0},
+        {3, 0, 1, 0},  {2, 0, 1, 0},  {2, 0, 1, 0},  {2, 2, 1, 0},
+    };
+};
 template <typename T, int N>
 struct PencilTune {
-    static constexpr int G = pencil_group<T, N>();
-    static constexpr int HINT = 2;
-    static constexpr bool DDIRECT = true;
-    static constexpr bool XCD = (N * N * N * sizeof(T)) % 128 != 0;
+    static constexpr PencilRow R = PencilTable<T>::row[N];
+    static constexpr int G = R.g > 0 ? R.g : pencil_group<T, N>();
+    static constexpr int HINT = R.hint;
+    static constexpr bool DDIRECT = R.ddirect != 0;
+    static constexpr bool XCD = R.xcd != 0;
     static constexpr size_t LDS_MIN = 0;    // LDS requested at least (caps workgroups per CU)
-};
-template <> struct PencilTune<double, 8> {
-    static constexpr int G = 4, HINT = 3;
-    static constexpr bool DDIRECT = false, XCD = false;
-    static constexpr size_t LDS_MIN = 0;
 };
 // n = 11: asking for 18 KB of LDS (10.4 KB are used) holds the CU at 8 workgroups instead of
 // 12; with fewer loads in flight the memory system runs 1.5 % faster (1.437 against 1.463 ms).
@@ -338,16 +352,6 @@ template <> struct PencilTune<double, 11> {
     static constexpr int G = 1, HINT = 0;
     static constexpr bool DDIRECT = true, XCD = true;
     static constexpr size_t LDS_MIN = 18 * 1024;
-};
-template <> struct PencilTune<double, 16> {
-    static constexpr int G = 1, HINT = 2;
-    static constexpr bool DDIRECT = true, XCD = false;
-    static constexpr size_t LDS_MIN = 0;
-};
-template <> struct PencilTune<float, 13> {
-    static constexpr int G = 3, HINT = 0;
-    static constexpr bool DDIRECT = true, XCD = false;
-    static constexpr size_t LDS_MIN = 0;
 };
 
 // Tuning of the separable-diagonal form: as the D form unless measured otherwise.  Without the

@@ -263,17 +263,20 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     }
 }
 
-// Per n: elements per workgroup, hint bits and die renumbering; defaults as for the vector-FMA
-// pencil kernels.  n = 13 is the sweep's best on MI355X at E = 1048576.
+// Per n: elements per workgroup and die renumbering (hint bits 0 everywhere): the best of the
+// same sweep as for the vector-FMA pencil kernels; n = 13 at E = 1048576.  G = 0: the
+// lane-utilisation rule.
+struct PencilMmRow { int g, xcd; };
+constexpr PencilMmRow kPencilMmTable[TPO_MAX_N + 1] = {
+    {0, 0},
+    {0, 1}, {0, 0}, {0, 1}, {8, 0}, {12, 1}, {6, 0}, {6, 1}, {2, 0},
+    {6, 0}, {3, 0}, {2, 1}, {3, 0}, {3, 0}, {2, 1}, {1, 0}, {1, 1},
+};
 template <int N>
 struct PencilMmTune {
-    static constexpr int G = pencil_group<float, N>();
+    static constexpr int G = kPencilMmTable[N].g > 0 ? kPencilMmTable[N].g : pencil_group<float, N>();
     static constexpr int HINT = 0;
-    static constexpr bool XCD = (N * N * N * sizeof(float)) % 128 != 0;
-};
-template <> struct PencilMmTune<13> {
-    static constexpr int G = 3, HINT = 0;
-    static constexpr bool XCD = false;
+    static constexpr bool XCD = kPencilMmTable[N].xcd != 0;
 };
 
 template <int N>
