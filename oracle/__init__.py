@@ -54,6 +54,9 @@ def _load():
         lib.tpo_oracle_ihelm_sep.argtypes = [dp] * 9 + [ctypes.c_int, ctypes.c_longlong,
                                                         ctypes.c_int]
         lib.tpo_oracle_ihelm_sep.restype = ctypes.c_int
+        lib.tpo_oracle_backward_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int,
+                                                   ctypes.c_longlong]
+        lib.tpo_oracle_backward_lifted.restype = ctypes.c_int
         lib.tpo_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -140,6 +143,18 @@ def forward(u, s_x, s_y, s_z) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"tpo_oracle_forward_lifted failed ({rc})")
     return t
+
+
+def backward(g, s_x, s_y, s_z) -> np.ndarray:
+    """Backward half only: ``v = (S_x (x) S_y (x) S_z) g``, lifted form."""
+    g, s_x, s_y, s_z = map(_f64, (g, s_x, s_y, s_z))
+    n = _check_shapes(g, s_x, s_y, s_z, None)
+    v = np.empty_like(g)
+    rc = _load().tpo_oracle_backward_lifted(_ptr(g), _ptr(s_x), _ptr(s_y), _ptr(s_z),
+                                            _ptr(v), n, g.shape[0])
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_backward_lifted failed ({rc})")
+    return v
 
 
 def max_rel_err_per_element(v_test, v_ref) -> float:

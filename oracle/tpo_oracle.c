@@ -214,6 +214,28 @@ int tpo_oracle_forward_lifted(const double *u, const double *Sx, const double *S
     return 0;
 }
 
+/* Backward half only, lifted form in the same axis order: v = (Sx (x) Sy (x) Sz) g, i.e. the
+ * forward sums of Sec. 5.2 with each matrix used untransposed. */
+int tpo_oracle_backward_lifted(const double *g, const double *Sx, const double *Sy,
+                               const double *Sz, double *v, int n, long long num_elems)
+{
+    if (n < 1 || n > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!g || !Sx || !Sy || !Sz || !v) return -1;
+    const size_t cube = (size_t)n * n * n;
+    double *p = (double *)malloc(cube * sizeof(double));
+    double *q = (double *)malloc(cube * sizeof(double));
+    if (!p || !q) { free(p); free(q); return -1; }
+    for (long long e = 0; e < num_elems; ++e) {
+        mode_product(Sz, 0, 2, n, g + (size_t)e * cube, p);
+        mode_product(Sy, 0, 1, n, p, q);
+        mode_product(Sx, 0, 0, n, q, v + (size_t)e * cube);
+    }
+    free(p);
+    free(q);
+    return 0;
+}
+
 int tpo_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -223,6 +223,33 @@ def test_workload_diagonal_matches_helmholtz_recipe():
     assert d.min() > 1 / 31.0 and d.max() < 1 / 0.3
 
 
+# --- p6b: the two halves on their own ---------------------------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 3, 5])
+def test_transform_halves_against_kronecker(n):
+    u, sx, sy, sz, _ = rand_inputs(n, 3, 6100 + n)
+    m = np.kron(np.kron(sx, sy), sz)
+    uf = u.reshape(3, -1)
+    fwd = (uf @ m).reshape(u.shape)          # rows: (M^T u_e)^T
+    bwd = (uf @ m.T).reshape(u.shape)        # rows: (M u_e)^T
+    assert np.allclose(oracle.forward(u, sx, sy, sz), fwd, rtol=0, atol=1e-13 * np.abs(fwd).max())
+    assert np.allclose(oracle.backward(u, sx, sy, sz), bwd, rtol=0, atol=1e-13 * np.abs(bwd).max())
+    # with three different non-symmetric matrices the two halves differ: a transposed matrix
+    # or swapped roles cannot pass both
+    if n > 1:
+        assert oracle.max_rel_err_per_element(oracle.backward(u, sx, sy, sz), fwd) > 1e-2
+
+
+def test_transform_halves_compose_to_the_operator():
+    n = 4
+    u, sx, sy, sz, d = rand_inputs(n, 5, 6200)
+    whole = oracle.ihelm_apply(u, sx, sy, sz, d)
+    parts = oracle.backward(d * oracle.forward(u, sx, sy, sz), sx, sy, sz)
+    assert np.array_equal(whole, parts)       # same routine, same order of operations
+    q = [wl.orthogonal_matrix(n, np.random.default_rng(6300 + a)) for a in range(3)]
+    back = oracle.backward(oracle.forward(u, *q), *q)
+    assert np.allclose(back, u, rtol=0, atol=1e-14)
+
+
 # --- p9: separable-diagonal form --------------------------------------------------------------
 def helmholtz_matrix(s, lam, mu):
     """Dense (A_x (x) I (x) I + I (x) A_y (x) I + I (x) I (x) A_z + mu I), A_d = S_d diag(lam_d) S_d^T."""
