@@ -68,9 +68,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
     ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma", "pencil_mm"])
-    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep"],
+    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep", "forward", "backward"],
                     help="ihelm: D read from HBM (the headline); ihelm_sep: D evaluated in the "
-                         "kernel from lam_x, lam_y, lam_z, mu (two HBM streams instead of three)")
+                         "kernel from lam_x, lam_y, lam_z, mu (two HBM streams instead of three); "
+                         "forward / backward: one half of the operator on its own")
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=131072)
@@ -103,7 +104,13 @@ def main() -> int:
                "pencil_mm": tpo.TPO_VARIANT_PENCIL_MM}[args.variant]
     dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
     sep = args.op == "ihelm_sep"
-    if sep:
+    half = args.op in ("forward", "backward")
+    if half:
+        if args.variant != "auto":
+            log("bench.py: the transform halves have one kernel family; --variant does not apply")
+            return 2
+        chosen = tpo.TPO_VARIANT_PENCIL
+    elif sep:
         chosen = variant or tpo.tpo_ihelm_sep_variant_for(w.n, dt)
     else:
         chosen = variant or tpo.tpo_ihelm_variant_for(w.n, dt, not w.distinct_s)
@@ -116,7 +123,7 @@ def main() -> int:
     tv = torch.empty_like(tu)
     tlam = [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in wl.sep_inputs(w)]
     torch.cuda.synchronize()
-    nfields = 2 if sep else 3
+    nfields = 2 if (sep or half) else 3
     log(f"[bench] {w.name} ({args.op}): inputs resident after {time.time() - t0:.1f}s "
         f"({3 * tu.numel() * tu.element_size() / 1e9:.2f} GB for u, D, v); variant {chosen_name}")
 
@@ -125,8 +132,13 @@ def main() -> int:
             tv.data_ptr())
     sep_ptrs = ptrs[:4] + tuple(t.data_ptr() for t in tlam) + (tv.data_ptr(),)
 
+    direction = tpo.TPO_FORWARD if args.op == "forward" else tpo.TPO_BACKWARD
+
     def step():
-        if sep:
+        if half:
+            rc = tpo.tpo_transform_apply(*ptrs[:4], ptrs[5], w.n, w.num_elems, dt, direction,
+                                         stream.cuda_stream)
+        elif sep:
             rc = tpo.tpo_ihelm_apply_sep_variant(*sep_ptrs, w.n, w.num_elems, dt,
                                                  stream.cuda_stream, variant)
         else:
@@ -158,7 +170,10 @@ def main() -> int:
     # algorithmic traffic: u and v, plus D when it is an input; the separable form adds
     # 3 adds and a division per point to the flop count
     alg_bytes = w.bytes_per_elem * w.num_elems * nfields // 3
-    alg_flop = (w.flop_per_elem + (4 * w.n ** 3 if sep else 0)) * w.num_elems
+    if half:
+        alg_flop = 6 * w.n ** 4 * w.num_elems
+    else:
+        alg_flop = (w.flop_per_elem + (4 * w.n ** 3 if sep else 0)) * w.num_elems
     achieved_gbs = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
     achieved_tflops = alg_flop / (avg_kernel_ms * 1e-3) / 1e12
     log(f"[bench] kernel avg {avg_kernel_ms:.4f} ms (min {min(kernel_ms):.4f}, max "
@@ -189,7 +204,10 @@ def main() -> int:
     torch.cuda.synchronize()
     sx, sy, sz = wl.direction_matrices(w)
     lo, hi = 0, min(64, w.num_elems)
-    if sep:
+    if half:
+        ref = (oracle.forward if args.op == "forward" else oracle.backward)(
+            wl.field_u(w, lo, hi), sx, sy, sz)
+    elif sep:
         ref = oracle.ihelm_apply_sep(wl.field_u(w, lo, hi), sx, sy, sz, *wl.sep_inputs(w, lo, hi))
     else:
         ref = oracle.ihelm_apply(wl.field_u(w, lo, hi), sx, sy, sz, wl.diagonal_d(w, lo, hi))
@@ -205,7 +223,15 @@ def main() -> int:
         ns = min(args.cpu_sample, w.num_elems)
         hu = wl.field_u(w, 0, ns)
         cores = oracle.max_threads()
-        if sep:
+        if half:
+            fn = oracle.forward if args.op == "forward" else oracle.backward
+            cores = 1                        # the oracle's transform halves are single-threaded
+            ns = min(ns, 16384)
+            hu = hu[:ns]
+            fn(hu[:256], sx, sy, sz)                                        # load + warm
+            t1 = time.perf_counter()
+            fn(hu, sx, sy, sz)
+        elif sep:
             hl = wl.sep_inputs(w, 0, ns)
             oracle.ihelm_apply_sep(hu[:256], sx, sy, sz, *hl[:3], hl[3][:256])   # load + warm
             t1 = time.perf_counter()
@@ -217,7 +243,7 @@ def main() -> int:
             oracle.ihelm_apply(hu, sx, sy, sz, hd)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": ns / cpu_s, "unit": "elements/s", "cores": cores, "kind": "oracle",
-               "sample": f"first {ns} elements of {w.name}, one pass, all host threads "
+               "sample": f"first {ns} elements of {w.name}, one pass, {cores} host thread(s) "
                          f"({cpu_s:.2f} s wall)",
                "gflops": ns * w.flop_per_elem / cpu_s / 1e9}
         log(f"[bench] CPU oracle baseline: {ns / cpu_s:.0f} elements/s on {cores} threads")
@@ -246,7 +272,8 @@ def main() -> int:
         "parity_max_rel_err_sample": err,
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                     "traffic": stored_traffic(w.name + (":sep" if sep else ""), chosen_name)},
+                     "traffic": stored_traffic(w.name + (":sep" if sep else ":" + args.op if half else ""),
+                                               chosen_name)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -47,6 +47,12 @@ typedef enum {
                                  (v_mfma_f32_4x4x1 with A broadcast) */
 } tpo_variant_t;
 
+/* Which half of the operator tpo_transform_apply evaluates. */
+typedef enum {
+    TPO_FORWARD = 0,   /* t = (S_x (x) S_y (x) S_z)^T u: sums over the FIRST index of each matrix */
+    TPO_BACKWARD = 1   /* t = (S_x (x) S_y (x) S_z) u:   sums over the SECOND index */
+} tpo_direction_t;
+
 #define TPO_MAX_N 16         /* points per direction supported: 1 .. TPO_MAX_N */
 
 /*
@@ -155,6 +161,21 @@ int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y,
                                 void *stream, int variant);
 int tpo_ihelm_sep_variant_for(int n, int dtype);
 int tpo_ihelm_sep_has_variant(int n, int dtype, int variant);
+
+/*
+ * tpo_transform_apply -- one half of the operator on its own, for e = 0 .. num_elems-1:
+ *
+ *   TPO_FORWARD   t_e[i,j,k] = sum_l sum_m sum_q  S_x[l,i] * S_y[m,j] * S_z[q,k] * u_e[l,m,q]
+ *   TPO_BACKWARD  t_e[i,j,k] = sum_l sum_m sum_q  S_x[i,l] * S_y[j,m] * S_z[k,q] * u_e[l,m,q]
+ *
+ * The forward transform is the worked example of reduction lifting in Sec. 5.2 of the paper
+ * (the triple sum evaluated as three one-dimensional sums); tpo_ihelm_apply is forward, scale by
+ * D_e, backward.  Arguments, layout, alignment, ownership and stream semantics as in
+ * tpo_ihelm_apply; t == u exactly is allowed, any other overlap of t with u or an S is
+ * TPO_ERR_ALIAS; direction other than TPO_FORWARD / TPO_BACKWARD is TPO_ERR_INVALID_ARG.
+ */
+int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const void *S_z, void *t,
+                        int n, long long num_elems, int dtype, int direction, void *stream);
 
 /*
  * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming

@@ -66,6 +66,14 @@ int tpo_create(void)
                         return TPO_ERR_DEVICE;
                     }
                 }
+        for (int dt = 0; dt < 2; ++dt)
+            for (int n = 1; n <= TPO_MAX_N; ++n) {
+                const tpo::TransformEntry *k = tpo::transform_entry(n, dt);
+                if (k && (k->prepare_forward() != hipSuccess || k->prepare_backward() != hipSuccess)) {
+                    (void)hipGetLastError();
+                    return TPO_ERR_DEVICE;
+                }
+            }
     }
     ++g_refs[dev];
     return TPO_OK;
@@ -125,6 +133,33 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
     }
     tpo::ApplyArgs a{u, S_x, S_y, S_z, D, v, num_elems, (hipStream_t)stream};
     if (k->launch(a) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    return TPO_OK;
+}
+
+int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const void *S_z, void *t,
+                        int n, long long num_elems, int dtype, int direction, void *stream)
+{
+    const int rc = tpo::validate_transform(u, S_x, S_y, S_z, t, n, num_elems, dtype, direction);
+    if (rc != TPO_OK) return rc;
+    const tpo::TransformEntry *k = tpo::transform_entry(n, dtype);
+    if (!k) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_NOT_INITIALIZED;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
+    }
+    tpo::TransformArgs a{u, S_x, S_y, S_z, t, num_elems, (hipStream_t)stream};
+    const hipError_t err = direction == TPO_FORWARD ? k->launch_forward(a) : k->launch_backward(a);
+    if (err != hipSuccess) {
         (void)hipGetLastError();
         return TPO_ERR_DEVICE;
     }

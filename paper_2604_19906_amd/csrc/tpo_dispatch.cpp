@@ -8,6 +8,8 @@ const KernelEntry *pencil_entry_f32(int n);
 const KernelEntry *mfma_entry_f64(int n);
 const KernelEntry *mfma_entry_f32(int n);
 const KernelEntry *pencil_mm_entry_f32(int n);
+const TransformEntry *transform_entry_f64(int n);
+const TransformEntry *transform_entry_f32(int n);
 
 const KernelEntry *pencil_entry(int n, int dtype)
 {
@@ -22,6 +24,11 @@ const KernelEntry *mfma_entry(int n, int dtype)
 const KernelEntry *pencil_mm_entry(int n, int dtype)
 {
     return dtype == TPO_F32 ? pencil_mm_entry_f32(n) : nullptr;
+}
+
+const TransformEntry *transform_entry(int n, int dtype)
+{
+    return dtype == TPO_F64 ? transform_entry_f64(n) : transform_entry_f32(n);
 }
 
 }  // namespace tpo

@@ -23,6 +23,21 @@ struct KernelEntry {
     hipError_t (*prepare)();
 };
 
+// The transform halves on their own (tpo_transform_apply).
+struct TransformArgs {
+    const void *u, *sx, *sy, *sz;
+    void *t;
+    long long num_elems;
+    hipStream_t stream;
+};
+struct TransformEntry {
+    hipError_t (*launch_forward)(const TransformArgs &);
+    hipError_t (*launch_backward)(const TransformArgs &);
+    hipError_t (*prepare_forward)();
+    hipError_t (*prepare_backward)();
+};
+const TransformEntry *transform_entry(int n, int dtype);
+
 // dtype index: 0 = f64, 1 = f32.  n in 1..TPO_MAX_N.  Returns nullptr when the family has
 // no kernel for that shape.
 const KernelEntry *pencil_entry(int n, int dtype);
@@ -33,6 +48,8 @@ const KernelEntry *pencil_mm_entry(int n, int dtype);   // fp32 only
 int validate_apply(const void *u, const void *sx, const void *sy, const void *sz,
                    const void *d, const void *v, int n, long long num_elems, int dtype,
                    int variant);
+int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
+                       const void *t, int n, long long num_elems, int dtype, int direction);
 int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
                        const void *v, int n, long long num_elems, int dtype, int variant);

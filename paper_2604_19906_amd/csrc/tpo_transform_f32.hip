@@ -1,0 +1,22 @@
+// Instantiations of the transform kernels (forward and backward half on their own) for float,
+// n = 1 .. 16.
+#include "tpo_transform.hpp"
+
+namespace tpo {
+
+const TransformEntry *transform_entry_f32(int n)
+{
+    static const TransformEntry table[TPO_MAX_N] = {
+        TPO_TRANSFORM_ENTRY(float, 1), TPO_TRANSFORM_ENTRY(float, 2),
+        TPO_TRANSFORM_ENTRY(float, 3), TPO_TRANSFORM_ENTRY(float, 4),
+        TPO_TRANSFORM_ENTRY(float, 5), TPO_TRANSFORM_ENTRY(float, 6),
+        TPO_TRANSFORM_ENTRY(float, 7), TPO_TRANSFORM_ENTRY(float, 8),
+        TPO_TRANSFORM_ENTRY(float, 9), TPO_TRANSFORM_ENTRY(float, 10),
+        TPO_TRANSFORM_ENTRY(float, 11), TPO_TRANSFORM_ENTRY(float, 12),
+        TPO_TRANSFORM_ENTRY(float, 13), TPO_TRANSFORM_ENTRY(float, 14),
+        TPO_TRANSFORM_ENTRY(float, 15), TPO_TRANSFORM_ENTRY(float, 16),
+    };
+    return (n >= 1 && n <= TPO_MAX_N) ? &table[n - 1] : nullptr;
+}
+
+}  // namespace tpo

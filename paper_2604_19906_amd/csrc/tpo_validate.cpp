@@ -42,6 +42,29 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
     return TPO_OK;
 }
 
+int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
+                       const void *t, int n, long long num_elems, int dtype, int direction)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (direction != TPO_FORWARD && direction != TPO_BACKWARD) return TPO_ERR_INVALID_ARG;
+    if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
+    if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+    if (!u || !sx || !sy || !sz || !t) return TPO_ERR_INVALID_ARG;
+    const size_t w = (dtype == TPO_F64) ? 8 : 4;
+    const void *ptrs[5] = {u, sx, sy, sz, t};
+    for (const void *p : ptrs)
+        if ((uintptr_t)p % w) return TPO_ERR_INVALID_ARG;
+    if ((unsigned long long)num_elems > (~(size_t)0 >> 16)) return TPO_ERR_INVALID_ARG;
+    const size_t field = (size_t)num_elems * n * n * n * w;
+    const size_t mat = (size_t)n * n * w;
+    if (t != u && overlaps(t, field, u, field)) return TPO_ERR_ALIAS;
+    if (overlaps(t, field, sx, mat) || overlaps(t, field, sy, mat) ||
+        overlaps(t, field, sz, mat))
+        return TPO_ERR_ALIAS;
+    return TPO_OK;
+}
+
 int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
                        const void *v, int n, long long num_elems, int dtype, int variant)

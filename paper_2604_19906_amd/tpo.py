@@ -14,6 +14,7 @@ TPO_F64, TPO_F32 = 0, 1
 TPO_OK = 0
 TPO_ERR_INVALID_ARG, TPO_ERR_UNSUPPORTED, TPO_ERR_NOT_INITIALIZED = -1, -2, -3
 TPO_ERR_DEVICE, TPO_ERR_ALIAS = -4, -5
+TPO_FORWARD, TPO_BACKWARD = 0, 1
 TPO_VARIANT_AUTO, TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA, TPO_VARIANT_PENCIL_MM = 0, 1, 2, 3
 TPO_MAX_N = 16
 
@@ -56,6 +57,8 @@ def lib():
         l.tpo_ihelm_sep_variant_for.restype = ci
         l.tpo_ihelm_sep_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_sep_has_variant.restype = ci
+        l.tpo_transform_apply.argtypes = [vp, vp, vp, vp, vp, ci, cll, ci, ci, vp]
+        l.tpo_transform_apply.restype = ci
         l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
         l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
@@ -116,6 +119,12 @@ def tpo_ihelm_sep_variant_for(n: int, dtype: int) -> int:
 
 def tpo_ihelm_sep_has_variant(n: int, dtype: int, variant: int) -> bool:
     return bool(lib().tpo_ihelm_sep_has_variant(int(n), int(dtype), int(variant)))
+
+
+def tpo_transform_apply(u, S_x, S_y, S_z, t, n, num_elems, dtype, direction, stream) -> int:
+    """Raw call of one half of the operator: integer device pointers in, status out."""
+    return lib().tpo_transform_apply(u, S_x, S_y, S_z, t, int(n), int(num_elems), int(dtype),
+                                     int(direction), stream)
 
 
 def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:
@@ -191,3 +200,30 @@ def apply_sep_tensors(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v=None,
                                       lam_z.data_ptr(), mu.data_ptr(), v.data_ptr(), n, e,
                                       dtype, stream, variant), "tpo_ihelm_apply_sep")
     return v
+
+
+def transform_tensors(u, S_x, S_y, S_z, direction: int, t=None):
+    """One half of the operator over torch device tensors; marshalling only."""
+    import torch
+
+    if u.dim() != 4 or not u.is_cuda:
+        raise ValueError("u must be a device tensor of shape [E,n,n,n]")
+    for x in (u, S_x, S_y, S_z):
+        if not x.is_contiguous() or x.dtype != u.dtype or not x.is_cuda:
+            raise ValueError("all tensors must be contiguous device tensors of one dtype")
+    e, n = u.shape[0], u.shape[1]
+    if tuple(u.shape[1:]) != (n, n, n):
+        raise ValueError("u must be [E,n,n,n]")
+    for s in (S_x, S_y, S_z):
+        if tuple(s.shape) != (n, n):
+            raise ValueError("S matrices must be [n,n]")
+    if t is None:
+        t = torch.empty_like(u)
+    elif (tuple(t.shape) != tuple(u.shape) or t.dtype != u.dtype or not t.is_contiguous()
+          or not t.is_cuda):
+        raise ValueError("t must match u")
+    dtype = {torch.float64: TPO_F64, torch.float32: TPO_F32}[u.dtype]
+    check(tpo_transform_apply(u.data_ptr(), S_x.data_ptr(), S_y.data_ptr(), S_z.data_ptr(),
+                              t.data_ptr(), n, e, dtype, direction,
+                              torch.cuda.current_stream().cuda_stream), "tpo_transform_apply")
+    return t

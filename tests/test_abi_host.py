@@ -121,6 +121,32 @@ def test_sep_argument_validation():
                                            None, tpo.TPO_VARIANT_MFMA) == tpo.TPO_ERR_UNSUPPORTED
 
 
+def test_transform_argument_validation():
+    n, e = 4, 10
+    keep, p = [], []
+    for _ in range(5):
+        a, addr = _buf(e * n ** 3 * 8)
+        keep.append(a)
+        p.append(addr)
+    u, sx, sy, sz, t = p
+    ap = tpo.tpo_transform_apply
+    F = tpo.TPO_FORWARD
+    assert ap(u, sx, sy, sz, t, 0, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, t, n, -2, tpo.TPO_F64, F, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, t, n, e, 9, F, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, t, n, e, tpo.TPO_F64, 5, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, t, 17, e, tpo.TPO_F32, F, None) == tpo.TPO_ERR_UNSUPPORTED
+    for k in range(5):
+        q = list(p)
+        q[k] = None
+        assert ap(*q, n, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u + 4, sx, sy, sz, t, n, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, u + 8, n, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, t + 8, sz, t, n, e, tpo.TPO_F64, tpo.TPO_BACKWARD, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, t, n, 0, tpo.TPO_F64, F, None) == tpo.TPO_OK
+    assert ap(u, sx, sy, sz, u, n, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_NOT_INITIALIZED
+
+
 def test_sep_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):
