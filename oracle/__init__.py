@@ -57,6 +57,12 @@ def _load():
         lib.tpo_oracle_backward_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int,
                                                    ctypes.c_longlong]
         lib.tpo_oracle_backward_lifted.restype = ctypes.c_int
+        lib.tpo_oracle_convection_direct.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_longlong]
+        lib.tpo_oracle_convection_direct.restype = ctypes.c_int
+        lib.tpo_oracle_convection_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_longlong, ctypes.c_int]
+        lib.tpo_oracle_convection_lifted.restype = ctypes.c_int
         lib.tpo_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -155,6 +161,37 @@ def backward(g, s_x, s_y, s_z) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"tpo_oracle_backward_lifted failed ({rc})")
     return v
+
+
+def _check_convection(p, m, d_vq, i_vq):
+    if d_vq.ndim != 2 or d_vq.shape != i_vq.shape:
+        raise ValueError("D_vq and I_vq must both be [nv,nq]")
+    nv, nq = d_vq.shape
+    if m.ndim != 4 or m.shape[1:] != (nq, nq, nq):
+        raise ValueError(f"M must be [E,{nq},{nq},{nq}], got {m.shape}")
+    if p.shape != (3, 3) + m.shape:
+        raise ValueError(f"P must be [3,3,E,{nq},{nq},{nq}], got {p.shape}")
+    return nv, nq, m.shape[0]
+
+
+def convection_apply(p, m, d_vq, i_vq, nthreads: int = 0, direct: bool = False) -> np.ndarray:
+    """Volume integral of the convective flux (Eq. 1 of the paper):
+    ``F[c,e,k,j,i] = sum_lmn (D[i,l] I[j,m] I[k,n] P[c,0] + I[i,l] D[j,m] I[k,n] P[c,1]
+    + I[i,l] I[j,m] D[k,n] P[c,2]) * M[e,n,m,l]`` with ``P[c,d]`` read at ``[e,n,m,l]``.
+    ``direct=True`` evaluates the six-deep sums as written (small sizes only).
+    Returns fp64 ``[3,E,nv,nv,nv]``."""
+    p, m, d_vq, i_vq = map(_f64, (p, m, d_vq, i_vq))
+    nv, nq, e = _check_convection(p, m, d_vq, i_vq)
+    f = np.empty((3, e, nv, nv, nv))
+    if direct:
+        rc = _load().tpo_oracle_convection_direct(_ptr(p), _ptr(m), _ptr(d_vq), _ptr(i_vq),
+                                                  _ptr(f), nv, nq, e)
+    else:
+        rc = _load().tpo_oracle_convection_lifted(_ptr(p), _ptr(m), _ptr(d_vq), _ptr(i_vq),
+                                                  _ptr(f), nv, nq, e, nthreads)
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_convection failed ({rc})")
+    return f
 
 
 def max_rel_err_per_element(v_test, v_ref) -> float:

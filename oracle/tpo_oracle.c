@@ -236,6 +236,127 @@ int tpo_oracle_backward_lifted(const double *g, const double *Sx, const double *
     return 0;
 }
 
+/* ------------------------------------------------------------------------------------------
+ * Volume integral of the convective flux (Eq. 1 of the paper; its index form is the one the
+ * paper prints for its DSL):
+ *
+ *   F[c,e,k,j,i] = sum_l sum_m sum_n (  Dm[i,l] * Im[j,m] * Im[k,n] * M[e,n,m,l] * P[c,0,e,n,m,l]
+ *                                     + Im[i,l] * Dm[j,m] * Im[k,n] * M[e,n,m,l] * P[c,1,e,n,m,l]
+ *                                     + Im[i,l] * Im[j,m] * Dm[k,n] * M[e,n,m,l] * P[c,2,e,n,m,l] )
+ *
+ * Dm, Im: [nv][nq] row-major (differentiation and interpolation from the nq quadrature points
+ * to the nv nodes of one direction); M: [E][nq][nq][nq]; P: [3][3][E][nq][nq][nq] (component c,
+ * direction, element); F: [3][E][nv][nv][nv].  The last cube axis (i, l) is the fastest.
+ *
+ * _direct: the six-deep sums as written.  _lifted: each term as three successive one-dimensional
+ * products (Sec. 2.2), innermost axis first, the three terms added at the end. */
+int tpo_oracle_convection_direct(const double *P, const double *M, const double *Dm,
+                                 const double *Im, double *F, int nv, int nq, long long num_elems)
+{
+    if (nv < 1 || nq < 1 || nv > TPO_ORACLE_MAX_N || nq > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!P || !M || !Dm || !Im || !F) return -1;
+    const size_t qc = (size_t)nq * nq * nq, vc = (size_t)nv * nv * nv;
+    for (int c = 0; c < 3; ++c)
+        for (long long e = 0; e < num_elems; ++e) {
+            const double *Me = M + (size_t)e * qc;
+            const double *P0 = P + (((size_t)c * 3 + 0) * num_elems + e) * qc;
+            const double *P1 = P + (((size_t)c * 3 + 1) * num_elems + e) * qc;
+            const double *P2 = P + (((size_t)c * 3 + 2) * num_elems + e) * qc;
+            double *Fe = F + ((size_t)c * num_elems + e) * vc;
+            for (int k = 0; k < nv; ++k)
+                for (int j = 0; j < nv; ++j)
+                    for (int i = 0; i < nv; ++i) {
+                        double acc = 0.0;
+                        for (int l = 0; l < nq; ++l)
+                            for (int m = 0; m < nq; ++m)
+                                for (int n = 0; n < nq; ++n) {
+                                    const size_t x = ((size_t)n * nq + m) * nq + l;
+                                    acc = acc + Dm[i * nq + l] * Im[j * nq + m] * Im[k * nq + n] * Me[x] * P0[x]
+                                              + Im[i * nq + l] * Dm[j * nq + m] * Im[k * nq + n] * Me[x] * P1[x]
+                                              + Im[i * nq + l] * Im[j * nq + m] * Dm[k * nq + n] * Me[x] * P2[x];
+                                }
+                        Fe[((size_t)k * nv + j) * nv + i] = acc;
+                    }
+        }
+    return 0;
+}
+
+/* out[k,j,i] = sum_{n,m,l} A2[k,n] A1[j,m] A0[i,l] in[n,m,l], one axis at a time (fastest first);
+ * tmp1, tmp2 hold nq*nq*nv and nq*nv*nv words. */
+static void three_products(const double *A2, const double *A1, const double *A0, int nv, int nq,
+                           const double *in, double *tmp1, double *tmp2, double *out)
+{
+    for (int n = 0; n < nq; ++n)
+        for (int m = 0; m < nq; ++m)
+            for (int i = 0; i < nv; ++i) {
+                double acc = 0.0;
+                for (int l = 0; l < nq; ++l) acc = acc + A0[i * nq + l] * in[((size_t)n * nq + m) * nq + l];
+                tmp1[((size_t)n * nq + m) * nv + i] = acc;
+            }
+    for (int n = 0; n < nq; ++n)
+        for (int j = 0; j < nv; ++j)
+            for (int i = 0; i < nv; ++i) {
+                double acc = 0.0;
+                for (int m = 0; m < nq; ++m) acc = acc + A1[j * nq + m] * tmp1[((size_t)n * nq + m) * nv + i];
+                tmp2[((size_t)n * nv + j) * nv + i] = acc;
+            }
+    for (int k = 0; k < nv; ++k)
+        for (int j = 0; j < nv; ++j)
+            for (int i = 0; i < nv; ++i) {
+                double acc = 0.0;
+                for (int n = 0; n < nq; ++n) acc = acc + A2[k * nq + n] * tmp2[((size_t)n * nv + j) * nv + i];
+                out[((size_t)k * nv + j) * nv + i] = acc;
+            }
+}
+
+int tpo_oracle_convection_lifted(const double *P, const double *M, const double *Dm,
+                                 const double *Im, double *F, int nv, int nq, long long num_elems,
+                                 int nthreads)
+{
+    if (nv < 1 || nq < 1 || nv > TPO_ORACLE_MAX_N || nq > TPO_ORACLE_MAX_N || num_elems < 0) return -1;
+    if (num_elems == 0) return 0;
+    if (!P || !M || !Dm || !Im || !F) return -1;
+    const size_t qc = (size_t)nq * nq * nq, vc = (size_t)nv * nv * nv;
+    const int big = nv > nq ? nv : nq;
+    const size_t wc = (size_t)big * big * big;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+#pragma omp parallel num_threads(nthreads)
+    {
+        double *w = (double *)malloc(6 * wc * sizeof(double));
+        if (!w) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+            double *in = w, *t1 = w + wc, *t2 = w + 2 * wc, *o0 = w + 3 * wc, *o1 = w + 4 * wc,
+                   *o2 = w + 5 * wc;
+#pragma omp for schedule(static) collapse(2)
+            for (int c = 0; c < 3; ++c)
+                for (long long e = 0; e < num_elems; ++e) {
+                    const double *Me = M + (size_t)e * qc;
+                    double *outs[3] = {o0, o1, o2};
+                    for (int dir = 0; dir < 3; ++dir) {
+                        const double *Pd = P + (((size_t)c * 3 + dir) * num_elems + e) * qc;
+                        for (size_t x = 0; x < qc; ++x) in[x] = Me[x] * Pd[x];
+                        three_products(dir == 2 ? Dm : Im, dir == 1 ? Dm : Im, dir == 0 ? Dm : Im,
+                                       nv, nq, in, t1, t2, outs[dir]);
+                    }
+                    double *Fe = F + ((size_t)c * num_elems + e) * vc;
+                    for (size_t x = 0; x < vc; ++x) Fe[x] = (o0[x] + o1[x]) + o2[x];
+                }
+        }
+        free(w);
+    }
+    return failed ? -1 : 0;
+}
+
 int tpo_oracle_max_threads(void)
 {
 #ifdef _OPENMP
