@@ -61,6 +61,103 @@ def stored_traffic(workload: str, variant: str):
     return ent.get("hbm_bytes_per_launch")
 
 
+def bench_convection(args, torch, tpo, wl) -> int:
+    """The convection volume term (Eq. 1 of the paper) on one of its synthetic configurations:
+    same timing scheme, its own algorithmic traffic (13 cubes per element)."""
+    import numpy as np
+    import oracle
+
+    if args.variant != "auto":
+        log("bench.py: the convection term has one kernel family; --variant does not apply")
+        return 2
+    w = wl.CONV_CONFIGS[args.workload if args.workload < len(wl.CONV_CONFIGS) else 1]
+    if args.elems:
+        w = wl.ConvWorkload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems)
+    dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
+    t0 = time.time()
+    tp, tm, td, ti = wl.conv_to_device(w)
+    tf = torch.empty((3, w.num_elems, w.n, w.n, w.n), dtype=tp.dtype, device="cuda")
+    torch.cuda.synchronize()
+    alg_bytes = w.bytes_per_elem * w.num_elems
+    alg_flop = w.flop_per_elem * w.num_elems
+    log(f"[bench] {w.name} (convection): inputs resident after {time.time() - t0:.1f}s "
+        f"({alg_bytes / 1e9:.2f} GB for P, M, F)")
+    stream = torch.cuda.current_stream()
+    ptrs = (tp.data_ptr(), tm.data_ptr(), td.data_ptr(), ti.data_ptr(), tf.data_ptr())
+
+    def step():
+        rc = tpo.tpo_convection_apply(*ptrs, w.n, w.n, w.num_elems, dt, stream.cuda_stream)
+        if rc != tpo.TPO_OK:
+            raise tpo.TpoError(rc, "tpo_convection_apply")
+
+    for _ in range(args.warmup):
+        step()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    kernel_ms = [a.elapsed_time(b) for a, b in evs]
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    achieved_gbs = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    achieved_tflops = alg_flop / (avg_kernel_ms * 1e-3) / 1e12
+    log(f"[bench] kernel avg {avg_kernel_ms:.4f} ms (min {min(kernel_ms):.4f}, max "
+        f"{max(kernel_ms):.4f}); wall/step {ms_per_step:.4f} ms; {achieved_gbs:.0f} GB/s; "
+        f"{achieved_tflops:.2f} TFLOP/s")
+
+    d, i = wl.conv_matrices(w)
+    hi = min(16, w.num_elems)
+    ref = oracle.convection_apply(wl.conv_flux(w, 0, hi), wl.conv_metric(w, 0, hi), d, i)
+    got = tf[:, :hi].cpu().numpy()
+    err = oracle.max_rel_err_per_element(got.reshape(-1, *got.shape[2:]),
+                                         ref.reshape(-1, *ref.shape[2:]))
+    tol = 1e-12 if w.dtype == "f64" else 2e-5
+    if not err <= tol:
+        log(f"[bench] PARITY FAILURE on the timed output: {err:.3e} > {tol}")
+        return 1
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        ns = min(4096, w.num_elems)
+        hp, hm = wl.conv_flux(w, 0, ns), wl.conv_metric(w, 0, ns)
+        cores = oracle.max_threads()
+        oracle.convection_apply(hp[:, :, :16], hm[:16], d, i)
+        t1 = time.perf_counter()
+        oracle.convection_apply(hp, hm, d, i)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": ns / cpu_s, "unit": "elements/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {ns} elements of {w.name}, one pass, all host threads "
+                         f"({cpu_s:.2f} s wall)"}
+        log(f"[bench] CPU oracle baseline: {ns / cpu_s:.0f} elements/s on {cores} threads")
+
+    out = {
+        "metric": "elements/s + GFLOP/s and % of binding roofline, convection volume term",
+        "value": w.num_elems / (ms_per_step * 1e-3), "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "op": "convection", "n": w.n, "num_elems": w.num_elems,
+                   "layout": "P [3,3,E,n,n,n], M [E,n,n,n], F [3,E,n,n,n]", "parallelism": "1 GPU"},
+        "gflops": alg_flop / (ms_per_step * 1e-3) / 1e9,
+        "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": min(kernel_ms),
+        "fp_frac_of_peak": achieved_tflops / FP_PEAK_TFLOPS[w.dtype],
+        "parity_max_rel_err_sample": err,
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": stored_traffic(w.name + ":convection", "pencil")},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    tpo.tpo_destroy()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,10 +165,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
     ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma", "pencil_mm"])
-    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep", "forward", "backward"],
+    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep", "forward", "backward", "convection"],
                     help="ihelm: D read from HBM (the headline); ihelm_sep: D evaluated in the "
                          "kernel from lam_x, lam_y, lam_z, mu (two HBM streams instead of three); "
-                         "forward / backward: one half of the operator on its own")
+                         "forward / backward: one half of the operator on its own; convection: the "
+                         "convection volume term (--workload indexes its own configurations)")
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=131072)
@@ -94,6 +192,9 @@ def main() -> int:
         return 1
     torch.cuda.set_device(0)
     tpo.check(tpo.tpo_create(), "tpo_create")      # raises if libtpo.so is missing
+
+    if args.op == "convection":
+        return bench_convection(args, torch, tpo, wl)
 
     w = wl.CONFIGS[args.workload]
     if args.elems:

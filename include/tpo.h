@@ -178,6 +178,28 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
                         int n, long long num_elems, int dtype, int direction, void *stream);
 
 /*
+ * tpo_convection_apply -- volume integral of the convective flux, Eq. 1 of the paper (the
+ * `convection` kernel of its Tables 1 and 2), in the index form the paper prints for its DSL:
+ *
+ *   F[c,e,k,j,i] = sum_l sum_m sum_n (  D_vq[i,l] I_vq[j,m] I_vq[k,n] M[e,n,m,l] P[c,0,e,n,m,l]
+ *                                     + I_vq[i,l] D_vq[j,m] I_vq[k,n] M[e,n,m,l] P[c,1,e,n,m,l]
+ *                                     + I_vq[i,l] I_vq[j,m] D_vq[k,n] M[e,n,m,l] P[c,2,e,n,m,l] )
+ *
+ *   P      DEVICE pointer, read only, [3][3][num_elems][n_q][n_q][n_q] C-contiguous: velocity
+ *          component c, flux direction (xi, eta, zeta), element, quadrature point (last index fastest)
+ *   M      DEVICE pointer, read only, [num_elems][n_q][n_q][n_q]: metric factor per quadrature point
+ *   D_vq, I_vq
+ *          DEVICE pointers, read only, [n_v][n_q] row-major: differentiation and interpolation
+ *          from the n_q quadrature points to the n_v nodes of one direction
+ *   F      DEVICE pointer, written, [3][num_elems][n_v][n_v][n_v]; must not overlap any input
+ *   n_v, n_q  1 .. TPO_MAX_N; this version has kernels for n_v == n_q only (otherwise
+ *          TPO_ERR_UNSUPPORTED)
+ *   num_elems, dtype, stream, alignment, ownership, error order: as in tpo_ihelm_apply.
+ */
+int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const void *I_vq, void *F,
+                         int n_v, int n_q, long long num_elems, int dtype, void *stream);
+
+/*
  * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming
  * kernel v[i] = u[i] * D[i], i < count, over flat DEVICE arrays of `dtype`.  It moves the
  * operator's algorithmic traffic (two reads and one write per word) and nothing else, so the

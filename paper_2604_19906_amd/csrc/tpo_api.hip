@@ -66,6 +66,13 @@ int tpo_create(void)
                         return TPO_ERR_DEVICE;
                     }
                 }
+        for (int n = 1; n <= TPO_MAX_N; ++n)
+            for (const tpo::ConvectionEntry *k :
+                 {tpo::convection_entry(n, TPO_F64), tpo::convection_entry(n, TPO_F32)})
+                if (k && k->prepare() != hipSuccess) {
+                    (void)hipGetLastError();
+                    return TPO_ERR_DEVICE;
+                }
         for (int dt = 0; dt < 2; ++dt)
             for (int n = 1; n <= TPO_MAX_N; ++n) {
                 const tpo::TransformEntry *k = tpo::transform_entry(n, dt);
@@ -132,6 +139,32 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
         if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
     }
     tpo::ApplyArgs a{u, S_x, S_y, S_z, D, v, num_elems, (hipStream_t)stream};
+    if (k->launch(a) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    return TPO_OK;
+}
+
+int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const void *I_vq, void *F,
+                         int n_v, int n_q, long long num_elems, int dtype, void *stream)
+{
+    const int rc = tpo::validate_convection(P, M, D_vq, I_vq, F, n_v, n_q, num_elems, dtype);
+    if (rc != TPO_OK) return rc;
+    const tpo::ConvectionEntry *k = tpo::convection_entry(n_q, dtype);
+    if (!k) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return TPO_ERR_NOT_INITIALIZED;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
+    }
+    tpo::ConvectionArgs a{P, M, D_vq, I_vq, F, num_elems, (hipStream_t)stream};
     if (k->launch(a) != hipSuccess) {
         (void)hipGetLastError();
         return TPO_ERR_DEVICE;

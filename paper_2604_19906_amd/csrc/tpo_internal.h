@@ -38,6 +38,19 @@ struct TransformEntry {
 };
 const TransformEntry *transform_entry(int n, int dtype);
 
+// The convection volume term (tpo_convection_apply).
+struct ConvectionArgs {
+    const void *p, *m, *d_vq, *i_vq;
+    void *f;
+    long long num_elems;
+    hipStream_t stream;
+};
+struct ConvectionEntry {
+    hipError_t (*launch)(const ConvectionArgs &);
+    hipError_t (*prepare)();
+};
+const ConvectionEntry *convection_entry(int n, int dtype);
+
 // dtype index: 0 = f64, 1 = f32.  n in 1..TPO_MAX_N.  Returns nullptr when the family has
 // no kernel for that shape.
 const KernelEntry *pencil_entry(int n, int dtype);
@@ -48,6 +61,8 @@ const KernelEntry *pencil_mm_entry(int n, int dtype);   // fp32 only
 int validate_apply(const void *u, const void *sx, const void *sy, const void *sz,
                    const void *d, const void *v, int n, long long num_elems, int dtype,
                    int variant);
+int validate_convection(const void *p, const void *m, const void *d_vq, const void *i_vq,
+                        const void *f, int n_v, int n_q, long long num_elems, int dtype);
 int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *t, int n, long long num_elems, int dtype, int direction);
 int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,

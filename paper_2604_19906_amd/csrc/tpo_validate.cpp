@@ -42,6 +42,28 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
     return TPO_OK;
 }
 
+int validate_convection(const void *p, const void *m, const void *d_vq, const void *i_vq,
+                        const void *f, int n_v, int n_q, long long num_elems, int dtype)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (n_v < 1 || n_q < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
+    if (n_v > TPO_MAX_N || n_q > TPO_MAX_N || n_v != n_q) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+    if (!p || !m || !d_vq || !i_vq || !f) return TPO_ERR_INVALID_ARG;
+    const size_t w = (dtype == TPO_F64) ? 8 : 4;
+    const void *ptrs[5] = {p, m, d_vq, i_vq, f};
+    for (const void *q : ptrs)
+        if ((uintptr_t)q % w) return TPO_ERR_INVALID_ARG;
+    if ((unsigned long long)num_elems > (~(size_t)0 >> 20)) return TPO_ERR_INVALID_ARG;
+    const size_t qcube = (size_t)num_elems * n_q * n_q * n_q * w;
+    const size_t vcube = (size_t)num_elems * n_v * n_v * n_v * w;
+    const size_t mat = (size_t)n_v * n_q * w;
+    if (overlaps(f, 3 * vcube, p, 9 * qcube) || overlaps(f, 3 * vcube, m, qcube) ||
+        overlaps(f, 3 * vcube, d_vq, mat) || overlaps(f, 3 * vcube, i_vq, mat))
+        return TPO_ERR_ALIAS;
+    return TPO_OK;
+}
+
 int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *t, int n, long long num_elems, int dtype, int direction)
 {

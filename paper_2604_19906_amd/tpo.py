@@ -59,6 +59,8 @@ def lib():
         l.tpo_ihelm_sep_has_variant.restype = ci
         l.tpo_transform_apply.argtypes = [vp, vp, vp, vp, vp, ci, cll, ci, ci, vp]
         l.tpo_transform_apply.restype = ci
+        l.tpo_convection_apply.argtypes = [vp, vp, vp, vp, vp, ci, ci, cll, ci, vp]
+        l.tpo_convection_apply.restype = ci
         l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
         l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
@@ -125,6 +127,12 @@ def tpo_transform_apply(u, S_x, S_y, S_z, t, n, num_elems, dtype, direction, str
     """Raw call of one half of the operator: integer device pointers in, status out."""
     return lib().tpo_transform_apply(u, S_x, S_y, S_z, t, int(n), int(num_elems), int(dtype),
                                      int(direction), stream)
+
+
+def tpo_convection_apply(P, M, D_vq, I_vq, F, n_v, n_q, num_elems, dtype, stream) -> int:
+    """Raw call of the convection volume term: integer device pointers in, status out."""
+    return lib().tpo_convection_apply(P, M, D_vq, I_vq, F, int(n_v), int(n_q), int(num_elems),
+                                      int(dtype), stream)
 
 
 def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:
@@ -227,3 +235,32 @@ def transform_tensors(u, S_x, S_y, S_z, direction: int, t=None):
                               t.data_ptr(), n, e, dtype, direction,
                               torch.cuda.current_stream().cuda_stream), "tpo_transform_apply")
     return t
+
+
+def convection_tensors(P, M, D_vq, I_vq, F=None):
+    """Convection volume term over torch device tensors (``P`` ``[3,3,E,nq,nq,nq]``, ``M``
+    ``[E,nq,nq,nq]``, ``D_vq``/``I_vq`` ``[nv,nq]``); marshalling only.  Returns ``F``
+    ``[3,E,nv,nv,nv]``."""
+    import torch
+
+    for x in (P, M, D_vq, I_vq):
+        if not x.is_contiguous() or x.dtype != P.dtype or not x.is_cuda:
+            raise ValueError("all tensors must be contiguous device tensors of one dtype")
+    if D_vq.dim() != 2 or tuple(I_vq.shape) != tuple(D_vq.shape):
+        raise ValueError("D_vq and I_vq must both be [nv,nq]")
+    nv, nq = D_vq.shape
+    if M.dim() != 4 or tuple(M.shape[1:]) != (nq, nq, nq):
+        raise ValueError("M must be [E,nq,nq,nq]")
+    e = M.shape[0]
+    if tuple(P.shape) != (3, 3, e, nq, nq, nq):
+        raise ValueError("P must be [3,3,E,nq,nq,nq]")
+    if F is None:
+        F = torch.empty((3, e, nv, nv, nv), dtype=P.dtype, device=P.device)
+    elif (tuple(F.shape) != (3, e, nv, nv, nv) or F.dtype != P.dtype or not F.is_contiguous()
+          or not F.is_cuda):
+        raise ValueError("F must be [3,E,nv,nv,nv]")
+    dtype = {torch.float64: TPO_F64, torch.float32: TPO_F32}[P.dtype]
+    check(tpo_convection_apply(P.data_ptr(), M.data_ptr(), D_vq.data_ptr(), I_vq.data_ptr(),
+                               F.data_ptr(), nv, nq, e, dtype,
+                               torch.cuda.current_stream().cuda_stream), "tpo_convection_apply")
+    return F

@@ -224,3 +224,145 @@ def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK, with_d: bo
     else:
         mats = (up(sx), up(sy), up(sz))
     return (tu, *mats, td) if with_d else (tu, *mats)
+
+
+# ------------------------------------------------------------------------------------------
+# Inputs of the convection volume term (Eq. 1 of the paper).  The paper's own inputs come
+# from a flow solver that is not available; these stand in for them: realistic one-dimensional
+# operators, a positive metric factor, uniformly distributed fluxes.
+
+@dataclass(frozen=True)
+class ConvWorkload:
+    """One synthetic configuration of the convection volume term (n_v = n_q = n)."""
+
+    name: str
+    index: int          # seed key, disjoint from the inverse-Helmholtz configurations
+    dtype: str
+    n: int
+    num_elems: int
+
+    @property
+    def np_dtype(self):
+        return np.float64 if self.dtype == "f64" else np.float32
+
+    @property
+    def word(self) -> int:
+        return 8 if self.dtype == "f64" else 4
+
+    @property
+    def bytes_per_elem(self) -> int:
+        """Algorithmic traffic per element: nine flux cubes and the metric in, three cubes out."""
+        return 13 * self.n ** 3 * self.word
+
+    @property
+    def flop_per_elem(self) -> int:
+        """Eight mode products per component (sum-factorised, terms merged) plus the metric
+        scale and the two merges."""
+        return 3 * (8 * 2 * self.n ** 4 + 5 * self.n ** 3)
+
+
+CONV_CONFIGS = (
+    ConvWorkload("conv0_f64_n7_E512", 20, "f64", 7, 512),
+    ConvWorkload("conv1_f64_n11_E32768", 21, "f64", 11, 32768),
+    ConvWorkload("conv2_f32_n13_E65536", 22, "f32", 13, 65536),
+    ConvWorkload("conv3_f64_n8_E65536", 23, "f64", 8, 65536),
+)
+
+CONV_BLOCK = 256
+_STREAM_CM, _STREAM_CP = 5, 6
+
+
+def conv_custom(n: int, num_elems: int, dtype: str = "f64", key: int = 120) -> ConvWorkload:
+    return ConvWorkload(f"conv_custom_{dtype}_n{n}_E{num_elems}", key, dtype, n, num_elems)
+
+
+def _lagrange_matrices(xq: np.ndarray, xv: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Values and first derivatives of the Lagrange basis on nodes ``xq`` at points ``xv``:
+    ``I[v,q] = l_q(xv[v])``, ``D[v,q] = l_q'(xv[v])`` (product formulas, fp64)."""
+    nq = len(xq)
+    interp = np.empty((len(xv), nq))
+    deriv = np.empty((len(xv), nq))
+    for q in range(nq):
+        others = [r for r in range(nq) if r != q]
+        den = np.prod([xq[q] - xq[r] for r in others]) if others else 1.0
+        for v, x in enumerate(xv):
+            interp[v, q] = np.prod([x - xq[r] for r in others]) / den if others else 1.0
+            total = 0.0
+            for s in others:
+                total += np.prod([x - xq[r] for r in others if r != s]) if len(others) > 1 else 1.0
+            deriv[v, q] = total / den
+    return interp, deriv
+
+
+def conv_matrices(w: ConvWorkload) -> Tuple[np.ndarray, np.ndarray]:
+    """``(D_vq, I_vq)``, each ``[n,n]``: differentiation and interpolation from the n
+    Chebyshev-Gauss points (quadrature side) to the n Chebyshev-Lobatto points (node side)."""
+    n = w.n
+    xq = -np.cos(np.pi * (2 * np.arange(n) + 1) / (2 * n))
+    xv = -np.cos(np.pi * np.arange(n) / (n - 1)) if n > 1 else np.zeros(1)
+    interp, deriv = _lagrange_matrices(xq, xv)
+    return deriv.astype(w.np_dtype), interp.astype(w.np_dtype)
+
+
+def conv_metric(w: ConvWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """Metric factor ``M[start:stop]`` ~ U(0.5, 2), ``[stop-start, n, n, n]``."""
+    stop = w.num_elems if stop is None else stop
+    n = w.n
+    out = np.empty((stop - start, n, n, n), dtype=w.np_dtype)
+    b = start // CONV_BLOCK
+    while b * CONV_BLOCK < stop:
+        lo, hi = max(start, b * CONV_BLOCK), min(stop, (b + 1) * CONV_BLOCK)
+        blk = _rng(w.index, _STREAM_CM, b).uniform(0.5, 2.0, (hi - b * CONV_BLOCK, n, n, n))
+        out[lo - start:hi - start] = blk[lo - b * CONV_BLOCK:]
+        b += 1
+    return out
+
+
+def conv_flux(w: ConvWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """Fluxes ``P[:, :, start:stop]`` ~ U(-1, 1), ``[3, 3, stop-start, n, n, n]``; every
+    (component, direction, block of elements) has its own seed."""
+    stop = w.num_elems if stop is None else stop
+    n = w.n
+    out = np.empty((3, 3, stop - start, n, n, n), dtype=w.np_dtype)
+    b = start // CONV_BLOCK
+    while b * CONV_BLOCK < stop:
+        lo, hi = max(start, b * CONV_BLOCK), min(stop, (b + 1) * CONV_BLOCK)
+        for c in range(3):
+            for d in range(3):
+                blk = _rng(w.index, _STREAM_CP, 3 * c + d, b).uniform(
+                    -1.0, 1.0, (hi - b * CONV_BLOCK, n, n, n))
+                out[c, d, lo - start:hi - start] = blk[lo - b * CONV_BLOCK:]
+        b += 1
+    return out
+
+
+def conv_inputs(w: ConvWorkload, start: int = 0, stop: int | None = None):
+    """``(P, M, D_vq, I_vq)`` for elements ``start..stop-1`` as host arrays."""
+    d_vq, i_vq = conv_matrices(w)
+    return conv_flux(w, start, stop), conv_metric(w, start, stop), d_vq, i_vq
+
+
+def conv_to_device(w: ConvWorkload, threads: int = 12, chunk: int = 4 * CONV_BLOCK):
+    """Device tensors ``(P, M, D_vq, I_vq)`` of a whole convection workload, generated block by
+    block on the host and copied into place."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import torch
+
+    e, n = w.num_elems, w.n
+    tdtype = torch.float64 if w.dtype == "f64" else torch.float32
+    tp = torch.empty((3, 3, e, n, n, n), dtype=tdtype, device="cuda")
+    tm = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")
+    spans = [(lo, min(e, lo + chunk)) for lo in range(0, e, chunk)]
+
+    def gen(span):
+        lo, hi = span
+        return lo, hi, conv_flux(w, lo, hi), conv_metric(w, lo, hi)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for lo, hi, hp, hm in ex.map(gen, spans):
+            tp[:, :, lo:hi].copy_(torch.from_numpy(hp))
+            tm[lo:hi].copy_(torch.from_numpy(hm))
+    d_vq, i_vq = conv_matrices(w)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return tp, tm, up(d_vq), up(i_vq)

@@ -147,6 +147,32 @@ def test_transform_argument_validation():
     assert ap(u, sx, sy, sz, u, n, e, tpo.TPO_F64, F, None) == tpo.TPO_ERR_NOT_INITIALIZED
 
 
+def test_convection_argument_validation():
+    n, e = 3, 4
+    keep, p = [], []
+    for size in (9 * e * n ** 3 * 8, e * n ** 3 * 8, n * n * 8, n * n * 8, 3 * e * n ** 3 * 8):
+        a, addr = _buf(size)
+        keep.append(a)
+        p.append(addr)
+    pp, m, d, i, f = p
+    ap = tpo.tpo_convection_apply
+    assert ap(pp, m, d, i, f, 0, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(pp, m, d, i, f, n, n, -1, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(pp, m, d, i, f, n, n, e, 2, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(pp, m, d, i, f, 17, 17, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    assert ap(pp, m, d, i, f, n, n + 1, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    for k in range(5):
+        q = list(p)
+        q[k] = None
+        assert ap(*q, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(pp + 4, m, d, i, f, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(pp, m, d, i, pp + 64, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(pp, m, d, i, m, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(pp, m, f + 8, i, f, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(pp, m, d, i, f, n, n, 0, tpo.TPO_F64, None) == tpo.TPO_OK
+    assert ap(pp, m, d, i, f, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_NOT_INITIALIZED
+
+
 def test_sep_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):

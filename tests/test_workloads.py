@@ -66,3 +66,20 @@ def test_sep_inputs_match_the_diagonal():
     w32 = wl.custom(4, 3, "f32", key=12, distinct_s=False)
     l32 = wl.sep_inputs(w32)
     assert all(a.dtype == np.float32 for a in l32) and l32[0] is l32[1]
+
+
+def test_convection_inputs():
+    w = wl.conv_custom(6, 600, "f64", key=31)
+    d, i = wl.conv_matrices(w)
+    # interpolation reproduces constants, differentiation annihilates them and is exact on x
+    assert np.allclose(i.sum(axis=1), 1.0) and np.allclose(d.sum(axis=1), 0.0, atol=1e-12)
+    xq = -np.cos(np.pi * (2 * np.arange(6) + 1) / 12)
+    xv = -np.cos(np.pi * np.arange(6) / 5)
+    assert np.allclose(i @ xq ** 3, xv ** 3) and np.allclose(d @ xq ** 3, 3 * xv ** 2)
+    p, m, _, _ = wl.conv_inputs(w, 250, 270)            # crosses a seed block
+    assert p.shape == (3, 3, 20, 6, 6, 6) and m.shape == (20, 6, 6, 6)
+    assert np.array_equal(p, wl.conv_flux(w)[:, :, 250:270])
+    assert np.array_equal(m, wl.conv_metric(w)[250:270])
+    assert m.min() >= 0.5 and m.max() <= 2.0 and np.abs(p).max() <= 1.0
+    assert not np.array_equal(p[0, 0], p[0, 1]) and not np.array_equal(p[0, 0], p[1, 0])
+    assert wl.conv_inputs(wl.conv_custom(4, 3, "f32"))[0].dtype == np.float32
