@@ -21,20 +21,52 @@
 #include <hip/hip_runtime.h>
 
 #include "tpo_pencil.hpp"
+#include "tpo_pencil_mm.hpp"
 
 namespace tpo {
 
-// Units per workgroup: best lane utilisation with at most 512 threads and 48 KB of LDS.
+// Workgroups are dealt round-robin to the 8 accelerator dies, each with its own L2.  With
+// SAME_DIE the batches of units are renumbered so that three consecutive batches run on ONE die
+// one after the other: block b (die b & 7, slot b >> 3) takes batch ((slot / 3) * 8 + die) * 3 +
+// slot % 3.  The three components of an element then find M_e in that die's L2 instead of
+// fetching it from HBM three times (measured: 12.1 -> 10.1 cubes read per element at n = 11).
+// The grid must be convection_grid<SAME_DIE>(number of batches); blocks past the end exit.
+template <bool SAME_DIE>
+__host__ __device__ inline long long convection_grid(long long nbatch)
+{
+    return SAME_DIE ? 24 * ((nbatch + 23) / 24) : nbatch;
+}
+template <bool SAME_DIE>
+__device__ __forceinline__ long long convection_batch()
+{
+    if constexpr (SAME_DIE) {
+        const long long die = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        return ((slot / 3) * 8 + die) * 3 + slot % 3;
+    } else {
+        return blockIdx.x;
+    }
+}
+
+// SPLIT (two LDS cubes per unit, two more barriers) pays once three cubes of a unit pass about
+// 20 KB (fp64 n = 11: 0.825 against 0.87 ms; fp32 n = 13: 1.73 against 1.82 ms; fp64 n = 8 with
+// 13 KB: 0.61 against 0.60 ms).
+template <typename T, int N>
+constexpr bool convection_split()
+{
+    return 3 * PencilShape<T, N, 1>::CUBE * sizeof(T) > 20 * 1024;
+}
+// Units per workgroup: best lane utilisation with at most 512 threads and 56 KB of LDS.
 template <typename T, int N>
 constexpr int convection_group()
 {
+    const long cubes = convection_split<T, N>() ? 2 : 3;
     int best = 1;
     long best_num = 0, best_den = 1;
     for (int g = 1; g <= 64; ++g) {
         const int p = g * N * N;
         const int nt = ((p + 63) / 64) * 64;
-        const long lds = 3L * g * PencilShape<T, N, 1>::CUBE * (long)sizeof(T);
-        if (nt > 512 || lds > 48 * 1024) break;
+        const long lds = cubes * g * PencilShape<T, N, 1>::CUBE * (long)sizeof(T);
+        if (g > 1 && (nt > 512 || lds > 56 * 1024)) break;
         if ((long)p * best_den > best_num * nt) {
             best = g;
             best_num = p;
@@ -44,7 +76,11 @@ constexpr int convection_group()
     return best;
 }
 
-template <typename T, int N, int G, int HINT>
+// HINT bit 0 / 1: non-temporal loads / stores.  XCD: the SAME_DIE renumbering above.
+// SPLIT: the third term's axis-l and axis-m products run after the first two terms have been
+// merged, in the LDS cube that merge frees: two cubes per unit instead of three (more
+// workgroups per CU) for two more barriers.
+template <typename T, int N, int G, int HINT, bool XCD, bool SPLIT = false>
 __global__ void __launch_bounds__((PencilShape<T, N, G>::NT))
 convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, const T *Dm_,
                          const T *Im_, T *__restrict__ F, long long num_elems)
@@ -63,17 +99,21 @@ convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, con
     const int hi = p / N;
     const int lo = p - hi * N;
     const long long units = 3 * num_elems;
-    const long long unit = (long long)blockIdx.x * G + g;
+    const long long nbatch = (units + G - 1) / G;
+    const long long batch = convection_batch<XCD>();
+    if (XCD && batch >= nbatch) return;                 // whole workgroup: no barrier is skipped
+    const long long unit = batch * G + g;
     const bool on = (tid < G * P) && (unit < units);
     const long long e = on ? unit / 3 : 0;
     const int c = on ? (int)(unit - 3 * e) : 0;
     constexpr size_t QC = (size_t)N * N * N;
 
-    T *c0 = lds + (size_t)(g < G ? g : 0) * 3 * CUBE;
+    T *c0 = lds + (size_t)(g < G ? g : 0) * (SPLIT ? 2 : 3) * CUBE;
     T *c1 = c0 + CUBE;
-    T *c2 = c1 + CUBE;
+    T *c2 = SPLIT ? c1 : c1 + CUBE;
 
     T x[N], y[N], z[N];
+    T x2[N];                     // SPLIT: M.P2 of the lane's (n,m) pencil, kept for later
 
     // axis l: lane (n,m) = (hi,lo) owns the n consecutive words [e][n][m][0..N-1] of M and P
     if (on) {
@@ -85,10 +125,15 @@ convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, con
             load_words<(HINT & 1) != 0>(Pq + cube + (size_t)(p * N), x);
 #pragma unroll
             for (int l = 0; l < N; ++l) x[l] *= mq[l];
-            mode_product<T, N, false>(dir == 0 ? Dm : Im, x, y);
-            T *dst = dir == 0 ? c0 : (dir == 1 ? c1 : c2);
+            if (SPLIT && dir == 2) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) dst[hi * PA + lo * PB + i] = y[i];
+                for (int l = 0; l < N; ++l) x2[l] = x[l];
+            } else {
+                mode_product<T, N, false>(dir == 0 ? Dm : Im, x, y);
+                T *dst = dir == 0 ? c0 : (dir == 1 ? c1 : c2);
+#pragma unroll
+                for (int i = 0; i < N; ++i) dst[hi * PA + lo * PB + i] = y[i];
+            }
         }
     }
     __syncthreads();
@@ -103,6 +148,17 @@ convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, con
         mode_product<T, N, false>(Dm, x, z);
 #pragma unroll
         for (int j = 0; j < N; ++j) c0[hi * PA + j * PB + lo] = y[j] + z[j];
+    }
+    if constexpr (SPLIT) {
+        __syncthreads();                      // every lane has read its pencils of cube 1
+        if (on) {                             // axis l of the third term: lane (n,m)
+            mode_product<T, N, false>(Im, x2, y);
+#pragma unroll
+            for (int i = 0; i < N; ++i) c2[hi * PA + lo * PB + i] = y[i];
+        }
+        __syncthreads();
+    }
+    if (on) {
 #pragma unroll
         for (int m = 0; m < N; ++m) x[m] = c2[hi * PA + m * PB + lo];
         mode_product<T, N, false>(Im, x, y);
@@ -125,18 +181,158 @@ convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, con
     }
 }
 
+// fp32 form with the mode products issued as 4x4x1 matrix-core outer products
+// (tpo_pencil_mm.hpp): same data movement; the coefficient tables of D and I (both used
+// untransposed) stay in registers for the whole kernel.  The matrix instructions ignore the
+// execution mask, so they run on every lane; idle lanes carry zeros or stale LDS words and
+// never store.
+template <int N, int G, int HINT, bool XCD, bool SPLIT = false>
+__global__ void __launch_bounds__((PencilShape<float, N, G>::NT))
+convection_mm_kernel(const float *__restrict__ Pq, const float *__restrict__ Mq,
+                     const float *__restrict__ Dm, const float *__restrict__ Im,
+                     float *__restrict__ F, long long num_elems)
+{
+    using Sh = PencilShape<float, N, G>;
+    using MS = MmShape<N>;
+    constexpr int P = Sh::P, PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE, NY = MS::NY;
+    extern __shared__ __align__(16) unsigned char tpo_lds[];
+    float *lds = reinterpret_cast<float *>(tpo_lds);
+
+    const TPO_CONSTANT float *Dc = (const TPO_CONSTANT float *)Dm;
+    const TPO_CONSTANT float *Ic = (const TPO_CONSTANT float *)Im;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int g = tid / P;
+    const int p = tid - g * P;
+    const int hi = p / N;
+    const int lo = p - hi * N;
+    const long long units = 3 * num_elems;
+    const long long nbatch = (units + G - 1) / G;
+    const long long batch = convection_batch<XCD>();
+    if (XCD && batch >= nbatch) return;
+    const long long unit = batch * G + g;
+    const bool on = (tid < G * P) && (unit < units);
+    const long long e = on ? unit / 3 : 0;
+    const int c = on ? (int)(unit - 3 * e) : 0;
+    constexpr size_t QC = (size_t)N * N * N;
+
+    // Lanes past the last pencil read (never write) slot 0; p < P keeps them inside the cube.
+    float *c0 = lds + (size_t)(g < G ? g : 0) * (SPLIT ? 2 : 3) * CUBE;
+    float *c1 = c0 + CUBE;
+    float *c2 = SPLIT ? c1 : c1 + CUBE;
+
+    float tab_d[MS::NTAB], tab_i[MS::NTAB];
+#pragma unroll
+    for (int t = 0; t < MS::NTAB; ++t) {
+        tab_d[t] = mm_coef<N>(Dm, false, t, lane);
+        tab_i[t] = mm_coef<N>(Im, false, t, lane);
+    }
+
+    float x[N], y[NY], z[NY], mq[N];
+    float x2[N];                 // SPLIT: M.P2 of the lane's (n,m) pencil, kept for later
+
+    // axis l: lane (n,m) = (hi,lo)
+    if (on) {
+        load_words<(HINT & 1) != 0>(Mq + (size_t)e * QC + (size_t)(p * N), mq);
+    } else {
+#pragma unroll
+        for (int l = 0; l < N; ++l) mq[l] = 0.0f;
+    }
+#pragma unroll
+    for (int dir = 0; dir < 3; ++dir) {
+        if (on) {
+            const size_t cube = ((size_t)(c * 3 + dir) * (size_t)num_elems + (size_t)e) * QC;
+            load_words<(HINT & 1) != 0>(Pq + cube + (size_t)(p * N), x);
+        } else {
+#pragma unroll
+            for (int l = 0; l < N; ++l) x[l] = 0.0f;
+        }
+#pragma unroll
+        for (int l = 0; l < N; ++l) x[l] *= mq[l];
+        if (SPLIT && dir == 2) {
+#pragma unroll
+            for (int l = 0; l < N; ++l) x2[l] = x[l];
+        } else {
+            if (dir == 0) mode_product_mm<N, false>(tab_d, Dc, x, y);
+            else mode_product_mm<N, false>(tab_i, Ic, x, y);
+            float *dst = dir == 0 ? c0 : (dir == 1 ? c1 : c2);
+            if (on) {
+#pragma unroll
+                for (int i = 0; i < N; ++i) dst[hi * PA + lo * PB + i] = y[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    // axis m: lane (n,i) = (hi,lo)
+#pragma unroll
+    for (int m = 0; m < N; ++m) x[m] = c0[hi * PA + m * PB + lo];
+    mode_product_mm<N, false>(tab_i, Ic, x, y);
+#pragma unroll
+    for (int m = 0; m < N; ++m) x[m] = c1[hi * PA + m * PB + lo];
+    mode_product_mm<N, false>(tab_d, Dc, x, z);
+    if (on) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) c0[hi * PA + j * PB + lo] = y[j] + z[j];
+    }
+    if constexpr (SPLIT) {
+        __syncthreads();                      // every lane has read its pencils of cube 1
+        mode_product_mm<N, false>(tab_i, Ic, x2, y);       // axis l of the third term: lane (n,m)
+        if (on) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) c2[hi * PA + lo * PB + i] = y[i];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int m = 0; m < N; ++m) x[m] = c2[hi * PA + m * PB + lo];
+    mode_product_mm<N, false>(tab_i, Ic, x, y);
+    if (on) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) c2[hi * PA + j * PB + lo] = y[j];
+    }
+    __syncthreads();
+
+    // axis n: lane (j,i) = (hi,lo)
+#pragma unroll
+    for (int n = 0; n < N; ++n) x[n] = c0[n * PA + hi * PB + lo];
+    mode_product_mm<N, false>(tab_i, Ic, x, y);
+#pragma unroll
+    for (int n = 0; n < N; ++n) x[n] = c2[n * PA + hi * PB + lo];
+    mode_product_mm<N, false>(tab_d, Dc, x, z);
+    if (on) {
+        const size_t out = ((size_t)c * (size_t)num_elems + (size_t)e) * QC;
+#pragma unroll
+        for (int k = 0; k < N; ++k) gstore<(HINT & 2) != 0>(F + out + (size_t)(k * P + p), y[k] + z[k]);
+    }
+}
+
 template <typename T, int N>
 struct ConvectionLauncher {
     static constexpr int G = convection_group<T, N>();
     using Sh = PencilShape<T, N, G>;
-    static constexpr size_t LDS = (size_t)3 * G * Sh::CUBE * sizeof(T);
-    static constexpr int HINT = 0;
+    static constexpr bool SPLIT = convection_split<T, N>();
+    static constexpr size_t LDS = (size_t)(SPLIT ? 2 : 3) * G * Sh::CUBE * sizeof(T);
+    // Sweep on MI355X (units per workgroup 1..6 x hints x renumbering; fp64 n = 8, 11, fp32
+    // n = 13): non-temporal stores are worth 3 to 8 %, non-temporal loads halve the rate (the
+    // per-lane runs share cache lines), more units per workgroup do not pay.
+    static constexpr int HINT = 2;
+    static constexpr bool XCD = G % 3 != 0;    // with G a multiple of 3 an element stays in one workgroup
 
-    static constexpr auto kernel() { return &convection_pencil_kernel<T, N, G, HINT>; }
+    // fp32, n >= 9: the 4x4x1 matrix-core form (the vector-FMA form is bound by FMA issue there,
+    // as for the inverse-Helmholtz operator).
+    static constexpr bool MM = sizeof(T) == 4 && N >= 9;
+
+    static constexpr auto kernel()
+    {
+        if constexpr (MM) return &convection_mm_kernel<N, G, HINT, XCD, SPLIT>;
+        else return &convection_pencil_kernel<T, N, G, HINT, XCD, SPLIT>;
+    }
 
     static hipError_t launch(const ConvectionArgs &a)
     {
-        const long long blocks = (3 * a.num_elems + G - 1) / G;
+        const long long blocks = convection_grid<XCD>((3 * a.num_elems + G - 1) / G);
         if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.p, (const T *)a.m, (const T *)a.d_vq, (const T *)a.i_vq,
