@@ -83,7 +83,7 @@ def bench_convection(args, torch, tpo, wl) -> int:
         return 2
     w = wl.CONV_CONFIGS[args.workload if args.workload < len(wl.CONV_CONFIGS) else 1]
     if args.elems:
-        w = wl.ConvWorkload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems)
+        w = wl.ConvWorkload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems, w.nq)
     dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
     t0 = time.time()
     tp, tm, td, ti = wl.conv_to_device(w)
@@ -97,13 +97,13 @@ def bench_convection(args, torch, tpo, wl) -> int:
     ptrs = (tp.data_ptr(), tm.data_ptr(), td.data_ptr(), ti.data_ptr(), tf.data_ptr())
 
     def step():
-        rc = tpo.tpo_convection_apply(*ptrs, w.n, w.n, w.num_elems, dt, stream.cuda_stream)
+        rc = tpo.tpo_convection_apply(*ptrs, w.n, w.q, w.num_elems, dt, stream.cuda_stream)
         if rc != tpo.TPO_OK:
             raise tpo.TpoError(rc, "tpo_convection_apply")
 
     # plain streaming kernel over three cubes of this workload (F is overwritten again below):
     # the streaming ceiling, and the calibration of the HBM counters in profiler runs
-    cube_words = tm.numel()
+    cube_words = min(tm.numel(), tf[0].numel())     # F cubes are smaller when n_v < n_q
     for _ in range(3):
         tpo.check(tpo.tpo_stream_scale(tp[0, 0].data_ptr(), tp[0, 1].data_ptr(), tf[0].data_ptr(),
                                        cube_words, dt, stream.cuda_stream), "tpo_stream_scale")
@@ -159,7 +159,8 @@ def bench_convection(args, torch, tpo, wl) -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": w.name, "op": "convection", "n": w.n, "num_elems": w.num_elems,
+        "config": {"workload": w.name, "op": "convection", "n": w.n, "n_q": w.q,
+                   "num_elems": w.num_elems,
                    "layout": "P [3,3,E,n,n,n], M [E,n,n,n], F [3,E,n,n,n]", "parallelism": "1 GPU"},
         "gflops": alg_flop / (ms_per_step * 1e-3) / 1e9,
         "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": min(kernel_ms),

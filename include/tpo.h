@@ -192,12 +192,17 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
  *          DEVICE pointers, read only, [n_v][n_q] row-major: differentiation and interpolation
  *          from the n_q quadrature points to the n_v nodes of one direction
  *   F      DEVICE pointer, written, [3][num_elems][n_v][n_v][n_v]; must not overlap any input
- *   n_v, n_q  1 .. TPO_MAX_N; this version has kernels for n_v == n_q only (otherwise
- *          TPO_ERR_UNSUPPORTED)
+ *   n_v, n_q  1 .. TPO_MAX_N.  Kernels exist for n_v == n_q (every n) and for the over-integration
+ *          shapes n_q in {n_v + 1, n_v + 2, ceil(3 n_v / 2)} with n_v in 2 .. 12 and n_q <= 16;
+ *          any other pair returns TPO_ERR_UNSUPPORTED (tpo_convection_has_shape tells)
  *   num_elems, dtype, stream, alignment, ownership, error order: as in tpo_ihelm_apply.
  */
 int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const void *I_vq, void *F,
                          int n_v, int n_q, long long num_elems, int dtype, void *stream);
+
+/* tpo_convection_has_shape -- 1 if tpo_convection_apply has a kernel for (n_v, n_q, dtype),
+ * else 0.  Pure host function. */
+int tpo_convection_has_shape(int n_v, int n_q, int dtype);
 
 /*
  * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming

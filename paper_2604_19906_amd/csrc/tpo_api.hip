@@ -14,7 +14,7 @@ constexpr int kMaxDevices = 64;
 std::mutex g_mu;
 int g_refs[kMaxDevices] = {0};
 
-// Family chosen by TPO_VARIANT_AUTO, from measurements on MI355X (see profiles/).
+// Family chosen by TPO_VARIANT_AUTO, from measurements on MI355X.
 int auto_variant(int n, int dtype, bool shared_s)
 {
     // Measured on MI355X at the sizes of the named workloads (ms per launch, pencil / MFMA):
@@ -68,11 +68,19 @@ int tpo_create(void)
                 }
         for (int n = 1; n <= TPO_MAX_N; ++n)
             for (const tpo::ConvectionEntry *k :
-                 {tpo::convection_entry(n, TPO_F64), tpo::convection_entry(n, TPO_F32)})
+                 {tpo::convection_entry(n, n, TPO_F64), tpo::convection_entry(n, n, TPO_F32)})
                 if (k && k->prepare() != hipSuccess) {
                     (void)hipGetLastError();
                     return TPO_ERR_DEVICE;
                 }
+        for (int dt = 0; dt < 2; ++dt)
+            for (int i = 0; i < tpo::convection_rect_count(dt); ++i) {
+                const tpo::ConvectionEntry *k = tpo::convection_rect_at(i, dt);
+                if (k && k->prepare() != hipSuccess) {
+                    (void)hipGetLastError();
+                    return TPO_ERR_DEVICE;
+                }
+            }
         for (int dt = 0; dt < 2; ++dt)
             for (int n = 1; n <= TPO_MAX_N; ++n) {
                 const tpo::TransformEntry *k = tpo::transform_entry(n, dt);
@@ -146,12 +154,21 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
     return TPO_OK;
 }
 
+int tpo_convection_has_shape(int n_v, int n_q, int dtype)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return 0;
+    if (n_v < 1 || n_q < 1 || n_v > TPO_MAX_N || n_q > TPO_MAX_N) return 0;
+    return tpo::convection_entry(n_v, n_q, dtype) != nullptr;
+}
+
 int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const void *I_vq, void *F,
                          int n_v, int n_q, long long num_elems, int dtype, void *stream)
 {
-    const int rc = tpo::validate_convection(P, M, D_vq, I_vq, F, n_v, n_q, num_elems, dtype);
+    const tpo::ConvectionEntry *k =
+        tpo_convection_has_shape(n_v, n_q, dtype) ? tpo::convection_entry(n_v, n_q, dtype) : nullptr;
+    const int rc = tpo::validate_convection(P, M, D_vq, I_vq, F, n_v, n_q, num_elems, dtype,
+                                            k != nullptr);
     if (rc != TPO_OK) return rc;
-    const tpo::ConvectionEntry *k = tpo::convection_entry(n_q, dtype);
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
 

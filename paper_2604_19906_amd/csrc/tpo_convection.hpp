@@ -308,6 +308,198 @@ convection_mm_kernel(const float *__restrict__ Pq, const float *__restrict__ Mq,
     }
 }
 
+// ---- rectangular form: n_q quadrature points and n_v nodes per direction, n_q != n_v ----------
+// Same scheme (vector-FMA pencils, two LDS cubes per unit, the third term's first two products
+// after the merge of the first two terms); the lane sets differ per axis: n_q*n_q pencils along
+// l, n_q*n_v along m, n_v*n_v along n.
+
+// y[i] = sum_l A[i][l] * x[l], A [NV][NQ] row-major, entries through the scalar data path.
+template <typename T, int NV, int NQ>
+__device__ __forceinline__ void mode_product_rect(const TPO_CONSTANT T *A, const T (&x)[NQ], T (&y)[NV])
+{
+    asm volatile("" : "+s"(A));
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        T acc = A[i * NQ] * x[0];
+#pragma unroll
+        for (int l = 1; l < NQ; ++l) acc = fma_(A[i * NQ + l], x[l], acc);
+        y[i] = acc;
+    }
+}
+
+template <typename T, int NV, int NQ, int G>
+struct ConvRectShape {
+    static constexpr int NB = NQ > NV ? NQ : NV;
+    static constexpr int L = NB * NB;                          // lanes per unit
+    static constexpr int NT = ((G * L + 63) / 64) * 64;
+    static constexpr int PB = (NV & 1) ? NV : NV + 1;          // row pitch (fastest axis: i)
+    static constexpr int PA = ((NB * PB) & 1) ? NB * PB : NB * PB + 1;
+    static constexpr int CUBE = NQ * PA;
+    static constexpr size_t LDS_BYTES = (size_t)2 * G * CUBE * sizeof(T);
+};
+
+template <typename T, int NV, int NQ, int G, int HINT, bool XCD>
+__global__ void __launch_bounds__((ConvRectShape<T, NV, NQ, G>::NT))
+convection_rect_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, const T *Dm_,
+                       const T *Im_, T *__restrict__ F, long long num_elems)
+{
+    using Sh = ConvRectShape<T, NV, NQ, G>;
+    constexpr int L = Sh::L, PA = Sh::PA, PB = Sh::PB, CUBE = Sh::CUBE;
+    extern __shared__ __align__(16) unsigned char tpo_lds[];
+    T *lds = reinterpret_cast<T *>(tpo_lds);
+
+    const TPO_CONSTANT T *Dm = (const TPO_CONSTANT T *)Dm_;
+    const TPO_CONSTANT T *Im = (const TPO_CONSTANT T *)Im_;
+
+    const int tid = threadIdx.x;
+    const int g = tid / L;
+    const int p = tid - g * L;
+    const long long units = 3 * num_elems;
+    const long long nbatch = (units + G - 1) / G;
+    const long long batch = convection_batch<XCD>();
+    if (XCD && batch >= nbatch) return;                 // whole workgroup: no barrier is skipped
+    const long long unit = batch * G + g;
+    const bool live = (tid < G * L) && (unit < units);
+    const long long e = live ? unit / 3 : 0;
+    const int c = live ? (int)(unit - 3 * e) : 0;
+    constexpr size_t QC = (size_t)NQ * NQ * NQ, VC = (size_t)NV * NV * NV;
+    const bool on_l = live && p < NQ * NQ;              // pencils along l: lane (n,m)
+    const bool on_m = live && p < NQ * NV;              // pencils along m: lane (n,i)
+    const bool on_n = live && p < NV * NV;              // pencils along n: lane (j,i)
+
+    T *c0 = lds + (size_t)(g < G ? g : 0) * 2 * CUBE;
+    T *c1 = c0 + CUBE;
+
+    T xq[NQ], x2[NQ], yv[NV], zv[NV];
+
+    // axis l: lane (n,m) owns the NQ consecutive words [e][n][m][0..NQ-1] of M and P
+    if (on_l) {
+        const int nn = p / NQ, mm = p - nn * NQ;
+        T mq[NQ];
+        load_words<(HINT & 1) != 0>(Mq + (size_t)e * QC + (size_t)(p * NQ), mq);
+#pragma unroll
+        for (int dir = 0; dir < 3; ++dir) {
+            const size_t cube = ((size_t)(c * 3 + dir) * (size_t)num_elems + (size_t)e) * QC;
+            load_words<(HINT & 1) != 0>(Pq + cube + (size_t)(p * NQ), xq);
+#pragma unroll
+            for (int l = 0; l < NQ; ++l) xq[l] *= mq[l];
+            if (dir == 2) {
+#pragma unroll
+                for (int l = 0; l < NQ; ++l) x2[l] = xq[l];
+            } else {
+                mode_product_rect<T, NV, NQ>(dir == 0 ? Dm : Im, xq, yv);
+                T *dst = dir == 0 ? c0 : c1;
+#pragma unroll
+                for (int i = 0; i < NV; ++i) dst[nn * PA + mm * PB + i] = yv[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    // axis m, first two terms merged: lane (n,i)
+    const int bn = p / NV, bi = p - bn * NV;
+    if (on_m) {
+#pragma unroll
+        for (int m = 0; m < NQ; ++m) xq[m] = c0[bn * PA + m * PB + bi];
+        mode_product_rect<T, NV, NQ>(Im, xq, yv);
+#pragma unroll
+        for (int m = 0; m < NQ; ++m) xq[m] = c1[bn * PA + m * PB + bi];
+        mode_product_rect<T, NV, NQ>(Dm, xq, zv);
+    }
+    __syncthreads();                                    // every pencil of cubes 0 and 1 has been read
+    if (on_m) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) c0[bn * PA + j * PB + bi] = yv[j] + zv[j];
+    }
+    // axis l of the third term, into the freed cube 1: lane (n,m)
+    if (on_l) {
+        const int nn = p / NQ, mm = p - nn * NQ;
+        mode_product_rect<T, NV, NQ>(Im, x2, yv);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) c1[nn * PA + mm * PB + i] = yv[i];
+    }
+    __syncthreads();
+    // axis m of the third term: lane (n,i)
+    if (on_m) {
+#pragma unroll
+        for (int m = 0; m < NQ; ++m) xq[m] = c1[bn * PA + m * PB + bi];
+        mode_product_rect<T, NV, NQ>(Im, xq, yv);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) c1[bn * PA + j * PB + bi] = yv[j];   // the lane's own pencil
+    }
+    __syncthreads();
+
+    // axis n: lane (j,i); stores are consecutive over lanes
+    if (on_n) {
+        const int jj = p / NV, ii = p - jj * NV;
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) xq[n] = c0[n * PA + jj * PB + ii];
+        mode_product_rect<T, NV, NQ>(Im, xq, yv);
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) xq[n] = c1[n * PA + jj * PB + ii];
+        mode_product_rect<T, NV, NQ>(Dm, xq, zv);
+        const size_t out = ((size_t)c * (size_t)num_elems + (size_t)e) * VC;
+#pragma unroll
+        for (int k = 0; k < NV; ++k)
+            gstore<(HINT & 2) != 0>(F + out + (size_t)(k * NV * NV + p), yv[k] + zv[k]);
+    }
+}
+
+template <typename T, int NV, int NQ>
+constexpr int convection_rect_group()
+{
+    int best = 1;
+    long best_num = 0, best_den = 1;
+    for (int g = 1; g <= 64; ++g) {
+        const int p = g * ConvRectShape<T, NV, NQ, 1>::L;
+        const int nt = ((p + 63) / 64) * 64;
+        const long lds = (long)g * (long)ConvRectShape<T, NV, NQ, 1>::LDS_BYTES;
+        if (g > 1 && (nt > 512 || lds > 56 * 1024)) break;
+        if ((long)p * best_den > best_num * nt) {
+            best = g;
+            best_num = p;
+            best_den = nt;
+        }
+    }
+    return best;
+}
+
+template <typename T, int NV, int NQ>
+struct ConvectionRectLauncher {
+    static constexpr int G = convection_rect_group<T, NV, NQ>();
+    using Sh = ConvRectShape<T, NV, NQ, G>;
+    static constexpr size_t LDS = Sh::LDS_BYTES;
+    static constexpr int HINT = 2;
+    static constexpr bool XCD = G % 3 != 0;
+
+    static constexpr auto kernel() { return &convection_rect_kernel<T, NV, NQ, G, HINT, XCD>; }
+
+    static hipError_t launch(const ConvectionArgs &a)
+    {
+        const long long blocks = convection_grid<XCD>((3 * a.num_elems + G - 1) / G);
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
+                           (const T *)a.p, (const T *)a.m, (const T *)a.d_vq, (const T *)a.i_vq,
+                           (T *)a.f, a.num_elems);
+        return hipGetLastError();
+    }
+
+    static hipError_t prepare()
+    {
+        if (LDS <= 48 * 1024) return hipSuccess;
+        return hipFuncSetAttribute((const void *)kernel(),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+    }
+};
+
+struct ConvectionRectEntry {
+    int n_v, n_q;
+    ConvectionEntry entry;
+};
+#define TPO_CONVECTION_RECT_ENTRY(T, NV, NQ)                                              \
+    ConvectionRectEntry { NV, NQ, ConvectionEntry { &ConvectionRectLauncher<T, NV, NQ>::launch, \
+                                                    &ConvectionRectLauncher<T, NV, NQ>::prepare } }
+
 template <typename T, int N>
 struct ConvectionLauncher {
     static constexpr int G = convection_group<T, N>();

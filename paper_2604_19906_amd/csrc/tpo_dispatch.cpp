@@ -28,9 +28,28 @@ const KernelEntry *pencil_mm_entry(int n, int dtype)
     return dtype == TPO_F32 ? pencil_mm_entry_f32(n) : nullptr;
 }
 
-const ConvectionEntry *convection_entry(int n, int dtype)
+const ConvectionEntry *convection_rect_entry_f64(int n_v, int n_q);
+const ConvectionEntry *convection_rect_entry_f32(int n_v, int n_q);
+int convection_rect_count_f64();
+int convection_rect_count_f32();
+const ConvectionEntry *convection_rect_at_f64(int k);
+const ConvectionEntry *convection_rect_at_f32(int k);
+
+const ConvectionEntry *convection_entry(int n_v, int n_q, int dtype)
 {
-    return dtype == TPO_F64 ? convection_entry_f64(n) : convection_entry_f32(n);
+    if (n_v == n_q) return dtype == TPO_F64 ? convection_entry_f64(n_v) : convection_entry_f32(n_v);
+    return dtype == TPO_F64 ? convection_rect_entry_f64(n_v, n_q)
+                            : convection_rect_entry_f32(n_v, n_q);
+}
+
+int convection_rect_count(int dtype)
+{
+    return dtype == TPO_F64 ? convection_rect_count_f64() : convection_rect_count_f32();
+}
+
+const ConvectionEntry *convection_rect_at(int k, int dtype)
+{
+    return dtype == TPO_F64 ? convection_rect_at_f64(k) : convection_rect_at_f32(k);
 }
 
 const TransformEntry *transform_entry(int n, int dtype)

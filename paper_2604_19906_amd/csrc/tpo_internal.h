@@ -49,7 +49,10 @@ struct ConvectionEntry {
     hipError_t (*launch)(const ConvectionArgs &);
     hipError_t (*prepare)();
 };
-const ConvectionEntry *convection_entry(int n, int dtype);
+// n_v == n_q: every n in 1..TPO_MAX_N; n_v != n_q: the instantiated over-integration shapes.
+const ConvectionEntry *convection_entry(int n_v, int n_q, int dtype);
+int convection_rect_count(int dtype);
+const ConvectionEntry *convection_rect_at(int k, int dtype);
 
 // dtype index: 0 = f64, 1 = f32.  n in 1..TPO_MAX_N.  Returns nullptr when the family has
 // no kernel for that shape.
@@ -62,7 +65,8 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
                    const void *d, const void *v, int n, long long num_elems, int dtype,
                    int variant);
 int validate_convection(const void *p, const void *m, const void *d_vq, const void *i_vq,
-                        const void *f, int n_v, int n_q, long long num_elems, int dtype);
+                        const void *f, int n_v, int n_q, long long num_elems, int dtype,
+                        bool has_kernel);   // has_kernel: a kernel exists for (n_v, n_q, dtype)
 int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *t, int n, long long num_elems, int dtype, int direction);
 int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,

@@ -14,7 +14,9 @@
 //   forward axis 0 (from global, lanes consecutive along (b,c): coalesced)
 //   forward axis 1, forward axis 2, scale by D_e, backward axis 2 (same registers),
 //   backward axis 1, backward axis 0 (to global, coalesced).
-// D_e is loaded coalesced together with u_e and parked in LDS until the scale.
+// D_e either arrives in its axis-2 pencil layout (each lane loads the n consecutive words of
+// its pencil) or coalesced like u_e and parked in LDS until the scale, or is evaluated in the
+// kernel from its separable form; see the template parameters of ihelm_pencil_kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 

@@ -43,11 +43,12 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
 }
 
 int validate_convection(const void *p, const void *m, const void *d_vq, const void *i_vq,
-                        const void *f, int n_v, int n_q, long long num_elems, int dtype)
+                        const void *f, int n_v, int n_q, long long num_elems, int dtype,
+                        bool has_kernel)
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
     if (n_v < 1 || n_q < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
-    if (n_v > TPO_MAX_N || n_q > TPO_MAX_N || n_v != n_q) return TPO_ERR_UNSUPPORTED;
+    if (n_v > TPO_MAX_N || n_q > TPO_MAX_N || !has_kernel) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
     if (!p || !m || !d_vq || !i_vq || !f) return TPO_ERR_INVALID_ARG;
     const size_t w = (dtype == TPO_F64) ? 8 : 4;

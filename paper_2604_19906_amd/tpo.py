@@ -61,6 +61,8 @@ def lib():
         l.tpo_transform_apply.restype = ci
         l.tpo_convection_apply.argtypes = [vp, vp, vp, vp, vp, ci, ci, cll, ci, vp]
         l.tpo_convection_apply.restype = ci
+        l.tpo_convection_has_shape.argtypes = [ci, ci, ci]
+        l.tpo_convection_has_shape.restype = ci
         l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
         l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
@@ -133,6 +135,10 @@ def tpo_convection_apply(P, M, D_vq, I_vq, F, n_v, n_q, num_elems, dtype, stream
     """Raw call of the convection volume term: integer device pointers in, status out."""
     return lib().tpo_convection_apply(P, M, D_vq, I_vq, F, int(n_v), int(n_q), int(num_elems),
                                       int(dtype), stream)
+
+
+def tpo_convection_has_shape(n_v: int, n_q: int, dtype: int) -> bool:
+    return bool(lib().tpo_convection_has_shape(int(n_v), int(n_q), int(dtype)))
 
 
 def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:

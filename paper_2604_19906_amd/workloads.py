@@ -233,13 +233,19 @@ def to_device(w: Workload, threads: int = 12, chunk: int = 2 * BLOCK, with_d: bo
 
 @dataclass(frozen=True)
 class ConvWorkload:
-    """One synthetic configuration of the convection volume term (n_v = n_q = n)."""
+    """One synthetic configuration of the convection volume term: ``n`` nodes and ``q``
+    quadrature points per direction (``nq = 0`` means as many as nodes)."""
 
     name: str
     index: int          # seed key, disjoint from the inverse-Helmholtz configurations
     dtype: str
     n: int
     num_elems: int
+    nq: int = 0
+
+    @property
+    def q(self) -> int:
+        return self.nq or self.n
 
     @property
     def np_dtype(self):
@@ -252,13 +258,14 @@ class ConvWorkload:
     @property
     def bytes_per_elem(self) -> int:
         """Algorithmic traffic per element: nine flux cubes and the metric in, three cubes out."""
-        return 13 * self.n ** 3 * self.word
+        return (10 * self.q ** 3 + 3 * self.n ** 3) * self.word
 
     @property
     def flop_per_elem(self) -> int:
         """Eight mode products per component (sum-factorised, terms merged) plus the metric
         scale and the two merges."""
-        return 3 * (8 * 2 * self.n ** 4 + 5 * self.n ** 3)
+        n, q = self.n, self.q
+        return 3 * (6 * q ** 3 * n + 6 * q ** 2 * n ** 2 + 4 * q * n ** 3 + 3 * q ** 3 + 2 * n ** 3)
 
 
 CONV_CONFIGS = (
@@ -266,14 +273,17 @@ CONV_CONFIGS = (
     ConvWorkload("conv1_f64_n11_E32768", 21, "f64", 11, 32768),
     ConvWorkload("conv2_f32_n13_E65536", 22, "f32", 13, 65536),
     ConvWorkload("conv3_f64_n8_E65536", 23, "f64", 8, 65536),
+    ConvWorkload("conv4_f64_n8_q12_E32768", 24, "f64", 8, 32768, 12),
 )
 
 CONV_BLOCK = 256
 _STREAM_CM, _STREAM_CP = 5, 6
 
 
-def conv_custom(n: int, num_elems: int, dtype: str = "f64", key: int = 120) -> ConvWorkload:
-    return ConvWorkload(f"conv_custom_{dtype}_n{n}_E{num_elems}", key, dtype, n, num_elems)
+def conv_custom(n: int, num_elems: int, dtype: str = "f64", key: int = 120,
+                nq: int = 0) -> ConvWorkload:
+    return ConvWorkload(f"conv_custom_{dtype}_n{n}_q{nq or n}_E{num_elems}", key, dtype, n,
+                        num_elems, nq)
 
 
 def _lagrange_matrices(xq: np.ndarray, xv: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
@@ -295,19 +305,19 @@ def _lagrange_matrices(xq: np.ndarray, xv: np.ndarray) -> Tuple[np.ndarray, np.n
 
 
 def conv_matrices(w: ConvWorkload) -> Tuple[np.ndarray, np.ndarray]:
-    """``(D_vq, I_vq)``, each ``[n,n]``: differentiation and interpolation from the n
+    """``(D_vq, I_vq)``, each ``[n,q]``: differentiation and interpolation from the q
     Chebyshev-Gauss points (quadrature side) to the n Chebyshev-Lobatto points (node side)."""
-    n = w.n
-    xq = -np.cos(np.pi * (2 * np.arange(n) + 1) / (2 * n))
+    n, q = w.n, w.q
+    xq = -np.cos(np.pi * (2 * np.arange(q) + 1) / (2 * q))
     xv = -np.cos(np.pi * np.arange(n) / (n - 1)) if n > 1 else np.zeros(1)
     interp, deriv = _lagrange_matrices(xq, xv)
     return deriv.astype(w.np_dtype), interp.astype(w.np_dtype)
 
 
 def conv_metric(w: ConvWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
-    """Metric factor ``M[start:stop]`` ~ U(0.5, 2), ``[stop-start, n, n, n]``."""
+    """Metric factor ``M[start:stop]`` ~ U(0.5, 2), ``[stop-start, q, q, q]``."""
     stop = w.num_elems if stop is None else stop
-    n = w.n
+    n = w.q
     out = np.empty((stop - start, n, n, n), dtype=w.np_dtype)
     b = start // CONV_BLOCK
     while b * CONV_BLOCK < stop:
@@ -319,10 +329,10 @@ def conv_metric(w: ConvWorkload, start: int = 0, stop: int | None = None) -> np.
 
 
 def conv_flux(w: ConvWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
-    """Fluxes ``P[:, :, start:stop]`` ~ U(-1, 1), ``[3, 3, stop-start, n, n, n]``; every
+    """Fluxes ``P[:, :, start:stop]`` ~ U(-1, 1), ``[3, 3, stop-start, q, q, q]``; every
     (component, direction, block of elements) has its own seed."""
     stop = w.num_elems if stop is None else stop
-    n = w.n
+    n = w.q
     out = np.empty((3, 3, stop - start, n, n, n), dtype=w.np_dtype)
     b = start // CONV_BLOCK
     while b * CONV_BLOCK < stop:
@@ -349,7 +359,7 @@ def conv_to_device(w: ConvWorkload, threads: int = 12, chunk: int = 4 * CONV_BLO
 
     import torch
 
-    e, n = w.num_elems, w.n
+    e, n = w.num_elems, w.q
     tdtype = torch.float64 if w.dtype == "f64" else torch.float32
     tp = torch.empty((3, 3, e, n, n, n), dtype=tdtype, device="cuda")
     tm = torch.empty((e, n, n, n), dtype=tdtype, device="cuda")

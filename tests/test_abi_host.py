@@ -160,7 +160,12 @@ def test_convection_argument_validation():
     assert ap(pp, m, d, i, f, n, n, -1, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
     assert ap(pp, m, d, i, f, n, n, e, 2, None) == tpo.TPO_ERR_INVALID_ARG
     assert ap(pp, m, d, i, f, 17, 17, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
-    assert ap(pp, m, d, i, f, n, n + 1, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    assert ap(pp, m, d, i, f, n, 16, e, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED   # no such shape
+    assert tpo.tpo_convection_has_shape(3, 3, tpo.TPO_F64) and tpo.tpo_convection_has_shape(3, 4, tpo.TPO_F32)
+    assert tpo.tpo_convection_has_shape(8, 12, tpo.TPO_F64)
+    assert not tpo.tpo_convection_has_shape(3, 16, tpo.TPO_F64)
+    assert not tpo.tpo_convection_has_shape(4, 3, tpo.TPO_F64)
+    assert not tpo.tpo_convection_has_shape(17, 17, tpo.TPO_F64)
     for k in range(5):
         q = list(p)
         q[k] = None

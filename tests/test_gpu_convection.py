@@ -47,6 +47,26 @@ def test_convection_all_n_small_batches(n, dtype):
         assert err <= TOL[dtype], f"convection n={n} {dtype} E={e}: err {err:.3e}"
 
 
+RECT_SHAPES = [(nv, nq) for nv in range(2, 13) for nq in sorted({nv + 1, nv + 2, (3 * nv + 1) // 2})
+               if nq <= 16]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("nv,nq", RECT_SHAPES)
+def test_convection_rectangular_shapes(nv, nq, dtype):
+    dt = tpo.TPO_F64 if dtype == "f64" else tpo.TPO_F32
+    assert tpo.tpo_convection_has_shape(nv, nq, dt)
+    for e in (1, 29):
+        w = wl.conv_custom(nv, e, dtype, key=1000 + 20 * nv + nq, nq=nq)
+        p, m, d, i = wl.conv_inputs(w)
+        assert d.shape == (nv, nq) and m.shape == (e, nq, nq, nq)
+        print(f"case convection nv={nv} nq={nq} {dtype} E={e}", flush=True)
+        got = run_convection(p, m, d, i)
+        assert got.shape == (3, e, nv, nv, nv)
+        err = cube_err(got, oracle.convection_apply(p, m, d, i))
+        assert err <= TOL[dtype], f"convection nv={nv} nq={nq} {dtype} E={e}: err {err:.3e}"
+
+
 def test_convection_general_matrices_and_direct_form():
     # nothing in the kernel relies on D and I being a differentiation / interpolation pair
     rng = np.random.default_rng(99)
@@ -66,11 +86,12 @@ def sample_spans(e):
     return spans
 
 
-@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
 def test_convection_full_size_configs(idx):
     w = wl.CONV_CONFIGS[idx]
     print(f"case convection {w.name}: generating", flush=True)
     tp, tm, td, ti = wl.conv_to_device(w)
+    assert tpo.tpo_convection_has_shape(w.n, w.q, tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32)
     tf = torch.full((3, w.num_elems, w.n, w.n, w.n), float("nan"), dtype=tp.dtype, device="cuda")
     tpo.convection_tensors(tp, tm, td, ti, tf)
     torch.cuda.synchronize()
@@ -112,4 +133,5 @@ def test_convection_status_codes_and_determinism():
     ap = tpo.tpo_convection_apply
     assert ap(*ptrs, out.data_ptr(), 6, 6, 0, tpo.TPO_F64, None) == tpo.TPO_OK
     assert ap(*ptrs, out.data_ptr(), 6, 5, 11, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    assert not tpo.tpo_convection_has_shape(6, 5, tpo.TPO_F64)
     assert ap(*ptrs, t[0].data_ptr(), 6, 6, 11, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
