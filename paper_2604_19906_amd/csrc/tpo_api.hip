@@ -23,9 +23,12 @@ int auto_variant(int n, int dtype, bool shared_s)
     // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
     if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
     // fp32: with 4x4x1 matrix-core products the pencil kernel leaves the vector-FMA bound
-    // (n=13, E=1048576: 5.5 against 6.0 ms).  Sweep over every n on 1 GiB fields, each family
-    // at its best setting: the 4x4x1 kernels win for n >= 9 (2 to 19 %), the vector-FMA ones
-    // for n <= 8 (2 to 8 %).
+    // (n=13, E=1048576: 5.5 against 6.0 ms).  All three families on 1 GiB fields, every n, each at
+    // its best setting (GB/s, vector-FMA pencil / 4x4x1 pencil / MFMA tiles): n=8 6079/5853/4790,
+    // n=9 5497/5484/3849, n=11 4939/5040/4440, n=12 4492/4934/4488, n=13 4559/5114/4197,
+    // n=14 3748/3990/4071, n=15 3873/4361/4607, n=16 4012/4878/5599: vector FMA up to n=8, the
+    // 4x4x1 kernels for n=9..13, the 16-wide tiles once n fills them (n >= 14).
+    if (dtype == TPO_F32 && n >= 14) return TPO_VARIANT_MFMA;
     if (dtype == TPO_F32 && n >= 9) return TPO_VARIANT_PENCIL_MM;
     return TPO_VARIANT_PENCIL;
 }
