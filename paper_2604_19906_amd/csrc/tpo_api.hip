@@ -224,10 +224,12 @@ int tpo_ihelm_sep_variant_for(int n, int dtype)
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
     if (n < 1) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
-    // The matrix-core tile kernels have no separable-diagonal form; otherwise as for the D form.
+    // The matrix-core tile kernels have no separable-diagonal form; where the D form takes them,
+    // this form takes the best pencil family instead (fp32 n >= 9: the 4x4x1 kernels).
     int var = auto_variant(n, dtype, false);
     const tpo::KernelEntry *k = lookup(n, dtype, var);
-    if (!k || !k->launch_sep) var = TPO_VARIANT_PENCIL;
+    if (!k || !k->launch_sep)
+        var = (dtype == TPO_F32 && n >= 9) ? TPO_VARIANT_PENCIL_MM : TPO_VARIANT_PENCIL;
     return var;
 }
 
