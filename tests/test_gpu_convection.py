@@ -121,6 +121,14 @@ def test_convection_full_size_configs(idx):
     print(f"  {w.name}: sampled {worst:.2e}, all cubes {worst_all:.2e}", flush=True)
 
 
+def test_convection_golden_file(repo_root):
+    import os
+    path = os.path.join(repo_root, "tests", "golden", "convection_f64_nv3_nq4_E2.txt")
+    want = np.array([float.fromhex(l) for l in open(path) if not l.startswith("#")])
+    got = run_convection(*wl.conv_inputs(wl.conv_custom(3, 2, "f64", key=78, nq=4)))
+    assert cube_err(got, want.reshape(got.shape)) <= 1e-12
+
+
 def test_convection_status_codes_and_determinism():
     w = wl.conv_custom(6, 11, "f64", key=900)
     t = [dev(a) for a in wl.conv_inputs(w)]

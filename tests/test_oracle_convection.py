@@ -115,3 +115,12 @@ def test_convection_linearity_and_shapes():
         oracle.convection_apply(p, m, d, i[:, :3])
     with pytest.raises(ValueError):
         oracle.convection_apply(p[:2], m, d, i)
+
+
+def test_convection_golden_regression(repo_root):
+    import os
+    from paper_2604_19906_amd import workloads as wl
+    path = os.path.join(repo_root, "tests", "golden", "convection_f64_nv3_nq4_E2.txt")
+    want = np.array([float.fromhex(l) for l in open(path) if not l.startswith("#")])
+    got = oracle.convection_apply(*wl.conv_inputs(wl.conv_custom(3, 2, "f64", key=78, nq=4)))
+    assert np.array_equal(got.ravel(), want)
