@@ -216,3 +216,24 @@ def test_status_codes_on_device():
     torch.cuda.synchronize()
     ref = oracle.ihelm_apply(u, sx, sy, sz, d)
     assert oracle.max_rel_err_per_element(tv.cpu().numpy(), ref) <= 1e-12
+
+
+def test_degenerate_inputs():
+    # identity matrices and unit diagonal: every product multiplies by 1 or adds 0, v == u bit for
+    # bit; zero field in, zero field out; a NaN stays inside its own element
+    for dtype, n in (("f64", 11), ("f32", 13), ("f64", 16), ("f32", 16), ("f64", 1)):
+        w = wl.custom(n, 53, dtype, key=1200 + n)
+        u = wl.field_u(w)
+        eye = np.eye(n, dtype=u.dtype)
+        ones = np.ones_like(u)
+        for name in variants_for(n, dtype):
+            assert np.array_equal(run(u, eye, eye, eye, ones, VARIANTS[name]), u), (dtype, n, name)
+            u2, sx, sy, sz, d = wl.make_inputs(w)
+            assert not run(np.zeros_like(u2), sx, sy, sz, d, VARIANTS[name]).any()
+            u3 = u2.copy()
+            u3[17, 0, 0, 0] = np.nan
+            got = run(u3, sx, sy, sz, d, VARIANTS[name])
+            bad = np.isnan(got).reshape(53, -1).any(axis=1)
+            assert bad[17] and bad.sum() == 1, (dtype, n, name)
+            clean = run(u2, sx, sy, sz, d, VARIANTS[name])
+            assert np.array_equal(np.delete(got, 17, axis=0), np.delete(clean, 17, axis=0))
