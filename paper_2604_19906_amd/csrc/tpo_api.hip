@@ -26,10 +26,11 @@ int auto_variant(int n, int dtype, bool shared_s)
     // (n=13, E=1048576: 5.5 against 6.0 ms).  All three families on 1 GiB fields, every n, each at
     // its best setting (GB/s, vector-FMA pencil / 4x4x1 pencil / MFMA tiles): n=8 6079/5853/4790,
     // n=9 5497/5484/3849, n=11 4939/5040/4440, n=12 4492/4934/4488, n=13 4559/5114/4197,
-    // n=14 3748/3990/4071, n=15 3873/4361/4607, n=16 4012/4878/5599: vector FMA up to n=8, the
-    // 4x4x1 kernels for n=9..13, the 16-wide tiles once n fills them (n >= 14).
+    // n=14 3748/3990/4071, n=15 3873/4361/4607, n=16 4012/4878/5599: vector FMA up to n=7, the
+    // 4x4x1 kernels for n=8..13 (n=8 with non-temporal u loads and stores: 6181/6401), the
+    // 16-wide tiles once n fills them (n >= 14).
     if (dtype == TPO_F32 && n >= 14) return TPO_VARIANT_MFMA;
-    if (dtype == TPO_F32 && n >= 9) return TPO_VARIANT_PENCIL_MM;
+    if (dtype == TPO_F32 && n >= 8) return TPO_VARIANT_PENCIL_MM;
     return TPO_VARIANT_PENCIL;
 }
 
@@ -225,11 +226,11 @@ int tpo_ihelm_sep_variant_for(int n, int dtype)
     if (n < 1) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
     // The matrix-core tile kernels have no separable-diagonal form; where the D form takes them,
-    // this form takes the best pencil family instead (fp32 n >= 9: the 4x4x1 kernels).
+    // this form takes the best pencil family instead (fp32 n >= 8: the 4x4x1 kernels).
     int var = auto_variant(n, dtype, false);
     const tpo::KernelEntry *k = lookup(n, dtype, var);
     if (!k || !k->launch_sep)
-        var = (dtype == TPO_F32 && n >= 9) ? TPO_VARIANT_PENCIL_MM : TPO_VARIANT_PENCIL;
+        var = (dtype == TPO_F32 && n >= 8) ? TPO_VARIANT_PENCIL_MM : TPO_VARIANT_PENCIL;
     return var;
 }
 

@@ -81,7 +81,8 @@ struct MfmaShape {
 // SAMES = true: the caller passed one matrix for all three directions (equal pointers); the A
 // operands are then held once instead of three times (for n = 16 in fp64 that is 32 VGPRs,
 // the difference between three and four wavefronts per SIMD).
-template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES, int WAVES>
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES, int WAVES,
+          bool XCD = false>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
 __attribute__((amdgpu_waves_per_eu(WAVES)))
 ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy,
@@ -194,7 +195,8 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 #define TPO_ZERO_ACC(ACC) \
     _Pragma("unroll") for (int j = 0; j < TPW; ++j) ACC[j] = acc_t{0, 0, 0, 0};
 
-    long long batch = blockIdx.x;
+    // XCD (one-shot grids only): batches renumbered per accelerator die as in tpo_pencil.hpp
+    long long batch = PERSIST ? (long long)blockIdx.x : pencil_batch<XCD>(nbatch);
     if (batch >= nbatch) return;
     load_u(batch);
     load_d(batch);
@@ -299,7 +301,7 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 }
 
 // Persistent grids are sized from the occupancy the runtime reports for the kernel.
-template <typename T, int N, int G, int NW, int HINT, bool PERSIST, int WAVES>
+template <typename T, int N, int G, int NW, int HINT, bool PERSIST, int WAVES, bool XCD = false>
 struct MfmaLauncher {
     using Sh = MfmaShape<T, N, G, NW>;
     static inline int wgs_per_device[2] = {0, 0};       // [SAMES]
@@ -309,12 +311,12 @@ struct MfmaLauncher {
     {
         const long long nbatch = (a.num_elems + G - 1) / G;
         if (nbatch <= 0 || nbatch > 0x7fffffffLL) return hipErrorInvalidValue;
-        long long blocks = nbatch;
+        long long blocks = PERSIST ? nbatch : pencil_grid<XCD>(nbatch);
         if (PERSIST) {
             if (wgs_per_device[SAMES] <= 0) return hipErrorNotInitialized;
             if (blocks > wgs_per_device[SAMES]) blocks = wgs_per_device[SAMES];
         }
-        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES>),
+        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD>),
                            dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems);
@@ -329,7 +331,7 @@ struct MfmaLauncher {
     template <bool SAMES>
     static hipError_t prepare_as()
     {
-        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES>;
+        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD>;
         if (Sh::LDS_BYTES > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)Sh::LDS_BYTES);

@@ -13,15 +13,16 @@ struct MfmaTune_f32 {
     static constexpr int HINT = 2;
     static constexpr bool PERSIST = false;
     static constexpr int WAVES = 1;
+    static constexpr bool XCD = false;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::launch,                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES, MfmaTune_f32<N>::XCD>::launch,                                   \
         nullptr,                                                                          \
         &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES>::prepare                                   \
+                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES, MfmaTune_f32<N>::XCD>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f32(int n)

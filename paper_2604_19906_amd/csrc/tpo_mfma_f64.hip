@@ -13,6 +13,7 @@ struct MfmaTune_f64 {
     static constexpr int HINT = 2;
     static constexpr bool PERSIST = false;
     static constexpr int WAVES = 1;
+    static constexpr bool XCD = false;
 };
 
 // n = 16: one workgroup per element, plain loads and stores (1.16 ms on 65536 elements with
@@ -24,6 +25,7 @@ struct MfmaTune_f64<16> {
     static constexpr int HINT = 0;
     static constexpr bool PERSIST = false;
     static constexpr int WAVES = 1;     // asking for a fourth wavefront per SIMD (125 VGPRs) measured equal
+    static constexpr bool XCD = false;  // die renumbering measured equal (1.280 against 1.282 ms)
 };
 // n = 11: persistent grid with register prefetch of the next element (1.69 ms against 1.87 ms).
 template <>
@@ -33,15 +35,16 @@ struct MfmaTune_f64<11> {
     static constexpr int HINT = 0;
     static constexpr bool PERSIST = true;
     static constexpr int WAVES = 1;
+    static constexpr bool XCD = false;
 };
 
 #define ENTRY(N)                                                                          \
     KernelEntry {                                                                         \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::launch,                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES, MfmaTune_f64<N>::XCD>::launch,                                   \
         nullptr,                                                                          \
         &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES>::prepare                                   \
+                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES, MfmaTune_f64<N>::XCD>::prepare                                   \
     }
 
 const KernelEntry *mfma_entry_f64(int n)

@@ -179,7 +179,8 @@ __device__ __forceinline__ void store_words(T *p, const T (&in)[K])
     if (q < K) gstore<NT>(p + q, in[q]);
 }
 
-// HINT bit 0: non-temporal loads of u and D; bit 1: non-temporal stores of v.
+// HINT bit 0: non-temporal coalesced loads (u, and D_e when it is loaded coalesced); bit 1:
+// non-temporal stores of v; bit 2: non-temporal loads of D_e's per-lane runs (DDIRECT).
 // DDIRECT = false: D_e is loaded coalesced with u_e and parked in LDS until the scale.
 // DDIRECT = true : every lane loads, at kernel start, the n consecutive words of D_e that
 //                  belong to its axis-2 pencil (no LDS for D_e: half the LDS per workgroup).
@@ -252,7 +253,7 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
             sep_ab = lam_x[hi] + lam_y[lo];
             sep_mu = mu[e];
         } else if constexpr (DDIRECT) {
-            load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);   // D_e[a][b][0..n-1]
+            load_words<(HINT & 4) != 0>(D + base + (size_t)(p * N), dd);   // D_e[a][b][0..n-1]
         } else {
 #pragma unroll
             for (int l = 0; l < N; ++l) dd[l] = gload<(HINT & 1) != 0>(D + base + (size_t)(l * P + p));
@@ -318,7 +319,7 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
 // Per (type, n): elements per workgroup G, hint bits, how D_e is brought in (1: straight into
 // its pencil layout, half the LDS; 0: coalesced and parked in LDS), and whether the workgroups
 // are renumbered per accelerator die.  One row per n = 1..16: the best of a sweep on MI355X over
-// G in {1,2,3,4,6,8,12,16,32} x hint bits x D mode x renumbering on 1 GiB fields; n = 8, 11, 16
+// G in {1,2,3,4,6,8,12,16,32} x hint bits x D mode x renumbering on 1 GiB fields; n = 8, 11
 // (fp64) and 13 (fp32) are the sweeps at the sizes of the named workloads.  n = 1 keeps the
 // lane-utilisation rule (G = 0 in the table).
 struct PencilRow { int g, hint, ddirect, xcd; };
@@ -326,17 +327,17 @@ template <typename T> struct PencilTable;
 template <> struct PencilTable<double> {
     static constexpr PencilRow row[TPO_MAX_N + 1] = {
         {0, 2, 1, 0},
-        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {4, 3, 0, 0},  {16, 0, 1, 0}, {16, 0, 1, 0},
-        {1, 3, 0, 1},  {4, 3, 0, 0},  {2, 0, 1, 0},  {2, 2, 1, 1},  {1, 0, 1, 1},  {3, 2, 1, 0},
-        {3, 0, 1, 0},  {1, 0, 1, 0},  {1, 0, 1, 0},  {1, 2, 1, 0},
+        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {4, 3, 0, 0},  {16, 0, 1, 0}, {1, 3, 1, 0},
+        {1, 3, 1, 0},  {4, 3, 0, 0},  {2, 0, 1, 0},  {1, 3, 1, 0},  {1, 0, 1, 1},  {3, 3, 1, 0},
+        {3, 0, 1, 0},  {1, 0, 1, 0},  {1, 0, 1, 0},  {1, 3, 1, 1},
     };
 };
 template <> struct PencilTable<float> {
     static constexpr PencilRow row[TPO_MAX_N + 1] = {
         {0, 2, 1, 0},
-        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 1}, {8, 2, 1, 0},  {16, 0, 1, 0}, {12, 0, 1, 0},
-        {4, 2, 1, 1},  {4, 3, 0, 0},  {3, 0, 1, 0},  {4, 0, 1, 1},  {2, 0, 1, 0},  {3, 2, 1, 0},
-        {3, 0, 1, 0},  {2, 0, 1, 0},  {2, 0, 1, 0},  {2, 2, 1, 0},
+        {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {8, 2, 1, 0},  {16, 0, 1, 0}, {12, 0, 1, 0},
+        {1, 3, 1, 1},  {2, 3, 1, 0},  {3, 0, 1, 0},  {2, 0, 1, 0},  {2, 0, 1, 0},  {3, 2, 1, 0},
+        {3, 0, 1, 0},  {2, 0, 1, 0},  {2, 0, 1, 0},  {1, 3, 1, 0},
     };
 };
 template <typename T, int N>

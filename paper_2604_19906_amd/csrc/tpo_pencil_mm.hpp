@@ -191,7 +191,7 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
             sep_ab = lam_x[hi] + lam_y[lo];
             sep_mu = mu[e];
         } else {
-            load_words<(HINT & 1) != 0>(D + base + (size_t)(p * N), dd);
+            load_words<(HINT & 4) != 0>(D + base + (size_t)(p * N), dd);
         }
     } else {
 #pragma unroll
@@ -263,19 +263,18 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     }
 }
 
-// Per n: elements per workgroup and die renumbering (hint bits 0 everywhere): the best of the
-// same sweep as for the vector-FMA pencil kernels; n = 13 at E = 1048576.  G = 0: the
-// lane-utilisation rule.
-struct PencilMmRow { int g, xcd; };
+// Per n: elements per workgroup, hint bits and die renumbering: the best of the same sweep as
+// for the vector-FMA pencil kernels; n = 13 at E = 1048576.  G = 0: the lane-utilisation rule.
+struct PencilMmRow { int g, hint, xcd; };
 constexpr PencilMmRow kPencilMmTable[TPO_MAX_N + 1] = {
-    {0, 0},
-    {0, 1}, {0, 0}, {0, 1}, {8, 0}, {12, 1}, {6, 0}, {6, 1}, {2, 0},
-    {6, 0}, {3, 0}, {2, 1}, {3, 0}, {3, 0}, {2, 1}, {1, 0}, {1, 1},
+    {0, 0, 0},
+    {0, 0, 1}, {0, 0, 0}, {0, 0, 1}, {8, 2, 0}, {12, 0, 0}, {12, 0, 0}, {6, 0, 0}, {1, 3, 0},
+    {6, 0, 0}, {3, 0, 1}, {2, 0, 0}, {3, 2, 0}, {3, 0, 0}, {2, 0, 0}, {1, 0, 1}, {1, 3, 0},
 };
 template <int N>
 struct PencilMmTune {
     static constexpr int G = kPencilMmTable[N].g > 0 ? kPencilMmTable[N].g : pencil_group<float, N>();
-    static constexpr int HINT = 0;
+    static constexpr int HINT = kPencilMmTable[N].hint;
     static constexpr bool XCD = kPencilMmTable[N].xcd != 0;
 };
 
