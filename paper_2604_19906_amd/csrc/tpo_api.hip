@@ -42,6 +42,18 @@ const tpo::KernelEntry *lookup(int n, int dtype, int variant)
     return nullptr;
 }
 
+// True when tpo_create has succeeded (and not been undone) on the calling thread's device.
+bool created_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return false;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_refs[dev] > 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -141,15 +153,7 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
 
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return TPO_ERR_NOT_INITIALIZED;
-    }
-    {
-        std::lock_guard<std::mutex> lock(g_mu);
-        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
-    }
+    if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ApplyArgs a{u, S_x, S_y, S_z, D, v, num_elems, (hipStream_t)stream};
     if (k->launch(a) != hipSuccess) {
         (void)hipGetLastError();
@@ -176,15 +180,7 @@ int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const v
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
 
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return TPO_ERR_NOT_INITIALIZED;
-    }
-    {
-        std::lock_guard<std::mutex> lock(g_mu);
-        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
-    }
+    if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ConvectionArgs a{P, M, D_vq, I_vq, F, num_elems, (hipStream_t)stream};
     if (k->launch(a) != hipSuccess) {
         (void)hipGetLastError();
@@ -202,15 +198,7 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
 
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return TPO_ERR_NOT_INITIALIZED;
-    }
-    {
-        std::lock_guard<std::mutex> lock(g_mu);
-        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
-    }
+    if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::TransformArgs a{u, S_x, S_y, S_z, t, num_elems, (hipStream_t)stream};
     const hipError_t err = direction == TPO_FORWARD ? k->launch_forward(a) : k->launch_backward(a);
     if (err != hipSuccess) {
@@ -256,15 +244,7 @@ int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y,
     if (!k || !k->launch_sep) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
 
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return TPO_ERR_NOT_INITIALIZED;
-    }
-    {
-        std::lock_guard<std::mutex> lock(g_mu);
-        if (g_refs[dev] <= 0) return TPO_ERR_NOT_INITIALIZED;
-    }
+    if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ApplyArgs a{u, S_x, S_y, S_z, nullptr, v, num_elems, (hipStream_t)stream,
                      lam_x, lam_y, lam_z, mu};
     if (k->launch_sep(a) != hipSuccess) {
