@@ -63,6 +63,9 @@ def _load():
         lib.tpo_oracle_convection_lifted.argtypes = [dp, dp, dp, dp, dp, ctypes.c_int, ctypes.c_int,
                                                      ctypes.c_longlong, ctypes.c_int]
         lib.tpo_oracle_convection_lifted.restype = ctypes.c_int
+        lib.tpo_oracle_ihelm_aniso.argtypes = [dp] * 6 + [ctypes.c_int] * 3 + [ctypes.c_longlong,
+                                                                               ctypes.c_int]
+        lib.tpo_oracle_ihelm_aniso.restype = ctypes.c_int
         lib.tpo_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -160,6 +163,24 @@ def backward(g, s_x, s_y, s_z) -> np.ndarray:
                                             _ptr(v), n, g.shape[0])
     if rc != 0:
         raise RuntimeError(f"tpo_oracle_backward_lifted failed ({rc})")
+    return v
+
+
+def ihelm_apply_aniso(u, s_x, s_y, s_z, d, direct: bool = False) -> np.ndarray:
+    """The operator on anisotropic elements: ``u``, ``D`` are ``[E,nx,ny,nz]``, ``S_x`` is
+    ``[nx,nx]``, ``S_y`` ``[ny,ny]``, ``S_z`` ``[nz,nz]``.  ``direct=True``: the six-deep sums."""
+    u, s_x, s_y, s_z, d = map(_f64, (u, s_x, s_y, s_z, d))
+    if u.ndim != 4 or d.shape != u.shape:
+        raise ValueError("u and D must both be [E,nx,ny,nz]")
+    _, nx, ny, nz = u.shape
+    for name, s, n in (("S_x", s_x, nx), ("S_y", s_y, ny), ("S_z", s_z, nz)):
+        if s.shape != (n, n):
+            raise ValueError(f"{name} must be [{n},{n}], got {s.shape}")
+    v = np.empty_like(u)
+    rc = _load().tpo_oracle_ihelm_aniso(_ptr(u), _ptr(s_x), _ptr(s_y), _ptr(s_z), _ptr(d),
+                                        _ptr(v), nx, ny, nz, u.shape[0], int(direct))
+    if rc != 0:
+        raise RuntimeError(f"tpo_oracle_ihelm_aniso failed ({rc})")
     return v
 
 

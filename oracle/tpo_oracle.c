@@ -237,6 +237,85 @@ int tpo_oracle_backward_lifted(const double *g, const double *Sx, const double *
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Anisotropic elements: nx, ny, nz points along axes 0, 1, 2 (u, D, v are [E][nx][ny][nz]; Sx is
+ * [nx][nx], Sy [ny][ny], Sz [nz][nz]).  Same operator, written on its own so that it does not
+ * lean on the cubic routine above: each half as three successive one-dimensional sums, axis 2
+ * first (Sec. 5.2), then the plain six-deep sums as a cross-check for small sizes. */
+static void aniso_product(const double *S, int transposed, int axis, const int dims[3],
+                          const double *in, double *out)
+{
+    const int n = dims[axis];
+    for (int a = 0; a < dims[0]; ++a)
+        for (int b = 0; b < dims[1]; ++b)
+            for (int c = 0; c < dims[2]; ++c) {
+                const int o = (axis == 0) ? a : (axis == 1) ? b : c;
+                double acc = 0.0;
+                for (int r = 0; r < n; ++r) {
+                    const int ia = (axis == 0) ? r : a, ib = (axis == 1) ? r : b, ic = (axis == 2) ? r : c;
+                    const double m = transposed ? S[r * n + o] : S[o * n + r];
+                    acc = acc + m * in[((size_t)ia * dims[1] + ib) * dims[2] + ic];
+                }
+                out[((size_t)a * dims[1] + b) * dims[2] + c] = acc;
+            }
+}
+
+int tpo_oracle_ihelm_aniso(const double *u, const double *Sx, const double *Sy, const double *Sz,
+                           const double *D, double *v, int nx, int ny, int nz,
+                           long long num_elems, int direct)
+{
+    if (nx < 1 || ny < 1 || nz < 1 || nx > TPO_ORACLE_MAX_N || ny > TPO_ORACLE_MAX_N ||
+        nz > TPO_ORACLE_MAX_N || num_elems < 0)
+        return -1;
+    if (num_elems == 0) return 0;
+    if (!u || !Sx || !Sy || !Sz || !D || !v) return -1;
+    const int dims[3] = {nx, ny, nz};
+    const size_t cube = (size_t)nx * ny * nz;
+    double *p = (double *)malloc(cube * sizeof(double));
+    double *q = (double *)malloc(cube * sizeof(double));
+    if (!p || !q) { free(p); free(q); return -1; }
+    for (long long e = 0; e < num_elems; ++e) {
+        const double *ue = u + (size_t)e * cube, *De = D + (size_t)e * cube;
+        double *ve = v + (size_t)e * cube;
+        if (!direct) {
+            aniso_product(Sz, 1, 2, dims, ue, p);
+            aniso_product(Sy, 1, 1, dims, p, q);
+            aniso_product(Sx, 1, 0, dims, q, p);
+            for (size_t x = 0; x < cube; ++x) q[x] = De[x] * p[x];
+            aniso_product(Sz, 0, 2, dims, q, p);
+            aniso_product(Sy, 0, 1, dims, p, q);
+            aniso_product(Sx, 0, 0, dims, q, ve);
+            continue;
+        }
+        for (int i = 0; i < nx; ++i)
+            for (int j = 0; j < ny; ++j)
+                for (int k = 0; k < nz; ++k) {
+                    double t = 0.0;
+                    for (int l = 0; l < nx; ++l)
+                        for (int m = 0; m < ny; ++m)
+                            for (int r = 0; r < nz; ++r)
+                                t = t + Sx[l * nx + i] * Sy[m * ny + j] * Sz[r * nz + k]
+                                        * ue[((size_t)l * ny + m) * nz + r];
+                    const size_t x = ((size_t)i * ny + j) * nz + k;
+                    p[x] = De[x] * t;
+                }
+        for (int i = 0; i < nx; ++i)
+            for (int j = 0; j < ny; ++j)
+                for (int k = 0; k < nz; ++k) {
+                    double acc = 0.0;
+                    for (int l = 0; l < nx; ++l)
+                        for (int m = 0; m < ny; ++m)
+                            for (int r = 0; r < nz; ++r)
+                                acc = acc + Sx[i * nx + l] * Sy[j * ny + m] * Sz[k * nz + r]
+                                            * p[((size_t)l * ny + m) * nz + r];
+                    ve[((size_t)i * ny + j) * nz + k] = acc;
+                }
+    }
+    free(p);
+    free(q);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
  * Volume integral of the convective flux (Eq. 1 of the paper; its index form is the one the
  * paper prints for its DSL):
  *
