@@ -262,6 +262,25 @@ int tpo_ihelm_apply_sep(const void *u, const void *S_x, const void *S_y, const v
                                        dtype, stream, TPO_VARIANT_AUTO);
 }
 
+int tpo_ihelm_apply_aniso(const void *u, const void *S_x, const void *S_y, const void *S_z,
+                          const void *D, void *v, int n_x, int n_y, int n_z, long long num_elems,
+                          int dtype, void *stream)
+{
+    if (n_x == n_y && n_y == n_z)       // cubic: the tuned kernels
+        return tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, n_x, num_elems, dtype, stream,
+                                       TPO_VARIANT_AUTO);
+    const int rc = tpo::validate_apply_aniso(u, S_x, S_y, S_z, D, v, n_x, n_y, n_z, num_elems, dtype);
+    if (rc != TPO_OK) return rc;
+    if (num_elems == 0) return TPO_OK;
+    if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
+    tpo::AnisoArgs a{u, S_x, S_y, S_z, D, v, n_x, n_y, n_z, num_elems, (hipStream_t)stream};
+    if (tpo::launch_ihelm_generic(a, dtype) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPO_ERR_DEVICE;
+    }
+    return TPO_OK;
+}
+
 int tpo_ihelm_apply(const void *u, const void *S_x, const void *S_y, const void *S_z,
                     const void *D, void *v, int n, long long num_elems, int dtype,
                     void *stream)

@@ -54,6 +54,16 @@ const ConvectionEntry *convection_entry(int n_v, int n_q, int dtype);
 int convection_rect_count(int dtype);
 const ConvectionEntry *convection_rect_at(int k, int dtype);
 
+// Anisotropic elements (tpo_ihelm_apply_aniso): the generic runtime-size kernel.
+struct AnisoArgs {
+    const void *u, *sx, *sy, *sz, *d;
+    void *v;
+    int nx, ny, nz;
+    long long num_elems;
+    hipStream_t stream;
+};
+hipError_t launch_ihelm_generic(const AnisoArgs &a, int dtype);
+
 // dtype index: 0 = f64, 1 = f32.  n in 1..TPO_MAX_N.  Returns nullptr when the family has
 // no kernel for that shape.
 const KernelEntry *pencil_entry(int n, int dtype);
@@ -67,6 +77,9 @@ int validate_apply(const void *u, const void *sx, const void *sy, const void *sz
 int validate_convection(const void *p, const void *m, const void *d_vq, const void *i_vq,
                         const void *f, int n_v, int n_q, long long num_elems, int dtype,
                         bool has_kernel);   // has_kernel: a kernel exists for (n_v, n_q, dtype)
+int validate_apply_aniso(const void *u, const void *sx, const void *sy, const void *sz,
+                         const void *d, const void *v, int nx, int ny, int nz, long long num_elems,
+                         int dtype);
 int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *t, int n, long long num_elems, int dtype, int direction);
 int validate_apply_sep(const void *u, const void *sx, const void *sy, const void *sz,

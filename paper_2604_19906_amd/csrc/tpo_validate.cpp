@@ -65,6 +65,29 @@ int validate_convection(const void *p, const void *m, const void *d_vq, const vo
     return TPO_OK;
 }
 
+int validate_apply_aniso(const void *u, const void *sx, const void *sy, const void *sz,
+                         const void *d, const void *v, int nx, int ny, int nz, long long num_elems,
+                         int dtype)
+{
+    if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
+    if (nx < 1 || ny < 1 || nz < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
+    if (nx > TPO_MAX_N || ny > TPO_MAX_N || nz > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
+    if (num_elems == 0) return TPO_OK;
+    if (!u || !sx || !sy || !sz || !d || !v) return TPO_ERR_INVALID_ARG;
+    const size_t w = (dtype == TPO_F64) ? 8 : 4;
+    const void *ptrs[6] = {u, sx, sy, sz, d, v};
+    for (const void *p : ptrs)
+        if ((uintptr_t)p % w) return TPO_ERR_INVALID_ARG;
+    if ((unsigned long long)num_elems > (~(size_t)0 >> 16)) return TPO_ERR_INVALID_ARG;
+    const size_t field = (size_t)num_elems * nx * ny * nz * w;
+    if (v != u && overlaps(v, field, u, field)) return TPO_ERR_ALIAS;
+    if (overlaps(v, field, d, field)) return TPO_ERR_ALIAS;
+    if (overlaps(v, field, sx, (size_t)nx * nx * w) || overlaps(v, field, sy, (size_t)ny * ny * w) ||
+        overlaps(v, field, sz, (size_t)nz * nz * w))
+        return TPO_ERR_ALIAS;
+    return TPO_OK;
+}
+
 int validate_transform(const void *u, const void *sx, const void *sy, const void *sz,
                        const void *t, int n, long long num_elems, int dtype, int direction)
 {

@@ -57,6 +57,8 @@ def lib():
         l.tpo_ihelm_sep_variant_for.restype = ci
         l.tpo_ihelm_sep_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_sep_has_variant.restype = ci
+        l.tpo_ihelm_apply_aniso.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, cll, ci, vp]
+        l.tpo_ihelm_apply_aniso.restype = ci
         l.tpo_transform_apply.argtypes = [vp, vp, vp, vp, vp, ci, cll, ci, ci, vp]
         l.tpo_transform_apply.restype = ci
         l.tpo_convection_apply.argtypes = [vp, vp, vp, vp, vp, ci, ci, cll, ci, vp]
@@ -123,6 +125,12 @@ def tpo_ihelm_sep_variant_for(n: int, dtype: int) -> int:
 
 def tpo_ihelm_sep_has_variant(n: int, dtype: int, variant: int) -> bool:
     return bool(lib().tpo_ihelm_sep_has_variant(int(n), int(dtype), int(variant)))
+
+
+def tpo_ihelm_apply_aniso(u, S_x, S_y, S_z, D, v, n_x, n_y, n_z, num_elems, dtype, stream) -> int:
+    """Raw call of the operator on anisotropic elements: integer device pointers in, status out."""
+    return lib().tpo_ihelm_apply_aniso(u, S_x, S_y, S_z, D, v, int(n_x), int(n_y), int(n_z),
+                                       int(num_elems), int(dtype), stream)
 
 
 def tpo_transform_apply(u, S_x, S_y, S_z, t, n, num_elems, dtype, direction, stream) -> int:
@@ -270,3 +278,30 @@ def convection_tensors(P, M, D_vq, I_vq, F=None):
                                F.data_ptr(), nv, nq, e, dtype,
                                torch.cuda.current_stream().cuda_stream), "tpo_convection_apply")
     return F
+
+
+def apply_aniso_tensors(u, S_x, S_y, S_z, D, v=None):
+    """The operator on anisotropic elements over torch device tensors (``u``, ``D``
+    ``[E,nx,ny,nz]``; ``S_x`` ``[nx,nx]``, ``S_y`` ``[ny,ny]``, ``S_z`` ``[nz,nz]``);
+    marshalling only."""
+    import torch
+
+    if u.dim() != 4 or not u.is_cuda or tuple(D.shape) != tuple(u.shape):
+        raise ValueError("u and D must be device tensors of shape [E,nx,ny,nz]")
+    for x in (u, S_x, S_y, S_z, D):
+        if not x.is_contiguous() or x.dtype != u.dtype or not x.is_cuda:
+            raise ValueError("all tensors must be contiguous device tensors of one dtype")
+    e, nx, ny, nz = u.shape
+    for s, n in ((S_x, nx), (S_y, ny), (S_z, nz)):
+        if tuple(s.shape) != (n, n):
+            raise ValueError("S matrices must be [nx,nx], [ny,ny], [nz,nz]")
+    if v is None:
+        v = torch.empty_like(u)
+    elif (tuple(v.shape) != tuple(u.shape) or v.dtype != u.dtype or not v.is_contiguous()
+          or not v.is_cuda):
+        raise ValueError("v must match u")
+    dtype = {torch.float64: TPO_F64, torch.float32: TPO_F32}[u.dtype]
+    check(tpo_ihelm_apply_aniso(u.data_ptr(), S_x.data_ptr(), S_y.data_ptr(), S_z.data_ptr(),
+                                D.data_ptr(), v.data_ptr(), nx, ny, nz, e, dtype,
+                                torch.cuda.current_stream().cuda_stream), "tpo_ihelm_apply_aniso")
+    return v

@@ -178,6 +178,26 @@ def test_convection_argument_validation():
     assert ap(pp, m, d, i, f, n, n, e, tpo.TPO_F64, None) == tpo.TPO_ERR_NOT_INITIALIZED
 
 
+def test_aniso_argument_validation():
+    keep, p = [], []
+    for _ in range(6):
+        a, addr = _buf(10 * 4 * 5 * 6 * 8)
+        keep.append(a)
+        p.append(addr)
+    u, sx, sy, sz, d, v = p
+    ap = tpo.tpo_ihelm_apply_aniso
+    assert ap(u, sx, sy, sz, d, v, 4, 0, 6, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, 4, 5, 17, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+    assert ap(u, sx, sy, sz, d, v, 4, 5, 6, -1, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, v, 4, 5, 6, 10, 4, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(None, sx, sy, sz, d, v, 4, 5, 6, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_INVALID_ARG
+    assert ap(u, sx, sy, sz, d, d, 4, 5, 6, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_ALIAS
+    assert ap(u, sx, sy, sz, d, v, 4, 5, 6, 0, tpo.TPO_F64, None) == tpo.TPO_OK
+    assert ap(u, sx, sy, sz, d, u, 4, 5, 6, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_NOT_INITIALIZED
+    # cubic shapes are tpo_ihelm_apply
+    assert ap(u, sx, sy, sz, d, v, 17, 17, 17, 10, tpo.TPO_F64, None) == tpo.TPO_ERR_UNSUPPORTED
+
+
 def test_sep_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):
