@@ -133,6 +133,17 @@ def test_full_size_configs(idx):
         print(f"  {w.name} {name}: sampled {worst:.2e}, all elements {worst_all:.2e}", flush=True)
 
 
+# small n with millions of elements: many workgroups per launch, several elements per
+# workgroup, a ragged last group; every element checked against the oracle
+@pytest.mark.parametrize("n,dtype,e", [(1, "f64", (1 << 22) + 3), (2, "f32", (1 << 22) + 5),
+                                       (3, "f64", (1 << 21) + 7), (4, "f32", (1 << 20) + 9)])
+def test_many_small_elements(n, dtype, e):
+    w = wl.custom(n, e, dtype, key=700 + n, distinct_s=True)
+    for name in variants_for(n, dtype):
+        print(f"case n={n} {dtype} E={e} variant={name}", flush=True)
+        check_against_oracle(w, name)
+
+
 def test_in_place_and_determinism():
     for dtype, n, e in (("f64", 11, 301), ("f32", 13, 150), ("f64", 16, 40), ("f64", 8, 77)):
         w = wl.custom(n, e, dtype, key=300 + n)
