@@ -1,122 +1,219 @@
-// Generic kernel of the inverse-Helmholtz operator for anisotropic elements: nx, ny, nz points
-// along axes 0, 1, 2, all runtime values in 1 .. 16.  The fallback behind
-// tpo_ihelm_apply_aniso for shapes that have no tuned instantiation (cubic shapes go to the
-// tuned families).  Same scheme as the pencil kernels, with runtime sizes: one workgroup of 256
-// lanes at most per element (the largest pencil count of the three axes, rounded up to whole
-// wavefronts), the cube in LDS, one pencil per lane for each mode product, matrix entries
-// through the scalar data path (their addresses are uniform), loops unrolled to a compile-time
-// bound (4, 8, 12 or 16, the smallest that covers the three sizes) with uniform guards so that
-// the pencil stays in registers.
+// Kernel of the inverse-Helmholtz operator for anisotropic elements: nx, ny, nz points along
+// axes 0, 1, 2, all runtime values in 1 .. 16.  It stands behind tpo_ihelm_apply_aniso for the
+// shapes that are not cubic (cubic shapes go to the tuned families).
+//
+// Same scheme as the pencil kernels: a workgroup takes g whole elements, the cube lives in LDS,
+// every lane owns one pencil per mode product, the matrix entries arrive in SGPRs.  What makes
+// it work for runtime sizes is that a mode product only needs the size of ITS axis at compile
+// time (for the unrolled FMAs and the batched scalar loads of the matrix); the other two sizes
+// only enter pencil counts and strides, which may be runtime values.  So every product is a
+// uniform switch over the size of its axis, and the kernel is compiled once per size class
+// (largest of the three sizes at most 4, 8, 12 or 16: the class bounds the registers).
+//
+// Order of the products, as in the pencil kernels: axis 0 first, on words read coalesced from
+// u_e (for a fixed index along axis 0 the lanes of that pass are consecutive words), axis 1,
+// then axis 2 forward, the scale and axis 2 backward on the lane's registers (each lane asked
+// for the nz consecutive words of D_e it needs when the kernel started), axis 1, and axis 0
+// last, stored coalesced to v_e.  Four barriers, no index arithmetic per word.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tpo_internal.h"
+#include "tpo_pencil.hpp"
 
 namespace tpo {
 
-#define TPO_CONSTANT_G __attribute__((address_space(4)))
-
 namespace {
 
-constexpr int MAX_NT = 256;
+constexpr int ANISO_MAX_NT = 256;
+// Non-temporal loads of u_e and stores of v_e, workgroups renumbered per die: the best or within
+// 2 % of the best of a sweep over eight shapes on MI355X (hint bits x renumbering x elements
+// per workgroup x LDS floor).
+constexpr int ANISO_HINT = 3;
+constexpr bool ANISO_XCD = true;
 
-__device__ __forceinline__ double gfma(double a, double b, double c) { return __builtin_fma(a, b, c); }
-__device__ __forceinline__ float gfma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
-
-// y[i] = sum_l M(i,l) x[l], i, l < n;  M(i,l) = S[l*n+i] when transposed, else S[i*n+l].
-template <typename T, int MAXN>
-__device__ __forceinline__ void product_rt(const TPO_CONSTANT_G T *S, bool transposed, int n,
-                                           const T (&x)[MAXN], T (&y)[MAXN])
+// f(integral_constant<int, n>) for the runtime n in 1 .. MAXN (uniform over the workgroup).
+template <int MAXN, typename F>
+__device__ __forceinline__ void dispatch_size(int n, F &&f)
 {
-#pragma unroll
-    for (int i = 0; i < MAXN; ++i) {
-        T acc = T(0);
-        if (i < n) {
-#pragma unroll
-            for (int l = 0; l < MAXN; ++l)
-                if (l < n) acc = gfma(transposed ? S[l * n + i] : S[i * n + l], x[l], acc);
-        }
-        y[i] = acc;
+#define TPO_SIZE_CASE(K)                                                       \
+    case K:                                                                    \
+        if constexpr (K <= MAXN) f(std::integral_constant<int, K>{});          \
+        break;
+    switch (n) {
+        TPO_SIZE_CASE(1) TPO_SIZE_CASE(2) TPO_SIZE_CASE(3) TPO_SIZE_CASE(4)
+        TPO_SIZE_CASE(5) TPO_SIZE_CASE(6) TPO_SIZE_CASE(7) TPO_SIZE_CASE(8)
+        TPO_SIZE_CASE(9) TPO_SIZE_CASE(10) TPO_SIZE_CASE(11) TPO_SIZE_CASE(12)
+        TPO_SIZE_CASE(13) TPO_SIZE_CASE(14) TPO_SIZE_CASE(15) TPO_SIZE_CASE(16)
+    default: break;
     }
+#undef TPO_SIZE_CASE
 }
 
-template <typename T, int MAXN>
-__global__ void __launch_bounds__(MAX_NT)
-ihelm_generic_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_, const T *__restrict__ D,
-                     T *v, int nx, int ny, int nz, long long num_elems)
+// LDS pitches: odd row pitch and odd plane pitch (in words) against bank conflicts.
+__host__ __device__ inline int aniso_pz(int nz) { return nz | 1; }
+__host__ __device__ inline int aniso_pyz(int ny, int nz) { return (ny * aniso_pz(nz)) | 1; }
+
+// HINT bits as in the pencil kernels: 1 non-temporal loads of u_e, 2 non-temporal stores of v_e,
+// 4 non-temporal loads of D_e.  XCD: workgroups renumbered per accelerator die (the grid must be
+// pencil_grid<XCD>(number of groups)).
+template <typename T, int MAXN, int HINT, bool XCD>
+__global__ void __launch_bounds__(ANISO_MAX_NT)
+ihelm_aniso_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_, const T *__restrict__ D,
+                   T *v, int nx, int ny, int nz, int g, long long num_elems, long long groups)
 {
     extern __shared__ __align__(16) unsigned char tpo_lds[];
     T *cube = reinterpret_cast<T *>(tpo_lds);
-    const TPO_CONSTANT_G T *Sx = (const TPO_CONSTANT_G T *)Sx_;
-    const TPO_CONSTANT_G T *Sy = (const TPO_CONSTANT_G T *)Sy_;
-    const TPO_CONSTANT_G T *Sz = (const TPO_CONSTANT_G T *)Sz_;
+    const TPO_CONSTANT T *Sx = (const TPO_CONSTANT T *)Sx_;
+    const TPO_CONSTANT T *Sy = (const TPO_CONSTANT T *)Sy_;
+    const TPO_CONSTANT T *Sz = (const TPO_CONSTANT T *)Sz_;
 
     const int tid = threadIdx.x;
-    const int NT = blockDim.x;
-    const long long e = blockIdx.x;
-    if (e >= num_elems) return;
-    const int total = nx * ny * nz;
-    const size_t base = (size_t)e * (size_t)total;
+    const long long batch = pencil_batch<XCD>(groups);
+    if (batch >= groups) return;                           // padding workgroup of the renumbering
+    const long long e0 = batch * g;
+    const long long left = num_elems - e0;
+    const int here = left < g ? (int)left : g;             // elements of this workgroup
+    const int pz = aniso_pz(nz), pyz = aniso_pyz(ny, nz);
+    const int cube_words = nx * pyz;
+    const int face = ny * nz;
+    const size_t total = (size_t)nx * face;
 
-    for (int i = tid; i < total; i += NT) cube[i] = u[base + i];
-    __syncthreads();
-
-    T x[MAXN], y[MAXN];
-    // one mode product along `axis` on the cube in LDS, in place (a lane rewrites its own pencil)
-    auto along = [&](int axis, const TPO_CONSTANT_G T *S, bool transposed) {
-        const int n = axis == 0 ? nx : (axis == 1 ? ny : nz);
-        const int pencils = total / n;
-        if (tid < pencils) {
-            int start, stride;
-            if (axis == 0) { start = tid; stride = ny * nz; }
-            else if (axis == 1) { const int a = tid / nz; start = a * ny * nz + (tid - a * nz); stride = nz; }
-            else { start = tid * nz; stride = 1; }
-#pragma unroll
-            for (int l = 0; l < MAXN; ++l) x[l] = l < n ? cube[start + l * stride] : T(0);
-            product_rt<T, MAXN>(S, transposed, n, x, y);
-#pragma unroll
-            for (int i = 0; i < MAXN; ++i)
-                if (i < n) cube[start + i * stride] = y[i];
-        }
-        __syncthreads();
+    // the lane's place in a pass with `pencils` pencils per element: element ge, pencil p
+    auto place = [&](int pencils, int &ge, int &p) {
+        ge = tid / pencils;
+        p = tid - ge * pencils;
+        return ge < here;
     };
 
-    along(0, Sx, true);
-    along(1, Sy, true);
-    // axis 2: forward, scale by D_e (each lane reads the nz consecutive words of its pencil),
-    // backward, all on the lane's registers
-    {
-        const int pencils = nx * ny;
-        if (tid < pencils) {
-            const int start = tid * nz;
-#pragma unroll
-            for (int l = 0; l < MAXN; ++l) x[l] = l < nz ? cube[start + l] : T(0);
-            product_rt<T, MAXN>(Sz, true, nz, x, y);
-#pragma unroll
-            for (int k = 0; k < MAXN; ++k) x[k] = k < nz ? y[k] * D[base + start + k] : T(0);
-            product_rt<T, MAXN>(Sz, false, nz, x, y);
-#pragma unroll
-            for (int k = 0; k < MAXN; ++k)
-                if (k < nz) cube[start + k] = y[k];
-        }
-        __syncthreads();
-    }
-    along(1, Sy, false);
-    along(0, Sx, false);
+    int ge2, p2;
+    const bool act2 = place(nx * ny, ge2, p2);              // lane (a, b): a pencil along axis 2
+    const int a2 = p2 / ny, b2 = p2 - a2 * ny;
+    T *row2 = cube + ge2 * cube_words + a2 * pyz + b2 * pz;
 
-    for (int i = tid; i < total; i += NT) v[base + i] = cube[i];
+    // D_e in the layout of the axis-2 pass, asked for before anything else
+    T dreg[MAXN];
+    if (act2)
+        dispatch_size<MAXN>(nz, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T t[N];
+            load_words<(HINT & 4) != 0, T, N>(D + (size_t)(e0 + ge2) * total + (size_t)p2 * nz, t);
+#pragma unroll
+            for (int k = 0; k < N; ++k) dreg[k] = t[k];
+        });
+
+    int ge1, p1;
+    const bool act1 = place(nx * nz, ge1, p1);              // lane (a, c): a pencil along axis 1
+    const int a1 = p1 / nz, c1 = p1 - a1 * nz;
+    T *col1 = cube + ge1 * cube_words + a1 * pyz + c1;
+
+    int ge0, p0;
+    const bool act0 = place(face, ge0, p0);                 // lane (b, c): a pencil along axis 0
+    const int b0 = p0 / nz, c0 = p0 - b0 * nz;
+    T *col0 = cube + ge0 * cube_words + b0 * pz + c0;
+    const size_t base0 = (size_t)(e0 + ge0) * total + p0;
+
+    // forward, axis 0, from global memory
+    if (act0)
+        dispatch_size<MAXN>(nx, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T x[N], y[N];
+#pragma unroll
+            for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base0 + (size_t)l * face);
+            mode_product<T, N, true>(Sx, x, y);
+#pragma unroll
+            for (int i = 0; i < N; ++i) col0[i * pyz] = y[i];
+        });
+    __syncthreads();
+    // forward, axis 1, in place
+    if (act1)
+        dispatch_size<MAXN>(ny, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T x[N], y[N];
+#pragma unroll
+            for (int m = 0; m < N; ++m) x[m] = col1[m * pz];
+            mode_product<T, N, true>(Sy, x, y);
+#pragma unroll
+            for (int m = 0; m < N; ++m) col1[m * pz] = y[m];
+        });
+    __syncthreads();
+    // axis 2: forward, scale by D_e, backward, in place
+    if (act2)
+        dispatch_size<MAXN>(nz, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T x[N], y[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) x[k] = row2[k];
+            mode_product<T, N, true>(Sz, x, y);
+#pragma unroll
+            for (int k = 0; k < N; ++k) y[k] *= dreg[k];
+            mode_product<T, N, false>(Sz, y, x);
+#pragma unroll
+            for (int k = 0; k < N; ++k) row2[k] = x[k];
+        });
+    __syncthreads();
+    // backward, axis 1, in place
+    if (act1)
+        dispatch_size<MAXN>(ny, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T x[N], y[N];
+#pragma unroll
+            for (int m = 0; m < N; ++m) x[m] = col1[m * pz];
+            mode_product<T, N, false>(Sy, x, y);
+#pragma unroll
+            for (int m = 0; m < N; ++m) col1[m * pz] = y[m];
+        });
+    __syncthreads();
+    // backward, axis 0, to global memory
+    if (act0)
+        dispatch_size<MAXN>(nx, [&](auto nc) {
+            constexpr int N = decltype(nc)::value;
+            T x[N], y[N];
+#pragma unroll
+            for (int l = 0; l < N; ++l) x[l] = col0[l * pyz];
+            mode_product<T, N, false>(Sx, x, y);
+#pragma unroll
+            for (int i = 0; i < N; ++i) gstore<(HINT & 2) != 0>(v + base0 + (size_t)i * face, y[i]);
+        });
+}
+
+// Elements per workgroup: the g with the best lane utilisation in the pass with the most
+// pencils, among those with at most 256 lanes and at most 40 KB of LDS.
+template <typename T>
+void aniso_shape(const AnisoArgs &a, int &g, int &nt, size_t &lds)
+{
+    int maxp = a.ny * a.nz;
+    if (a.nx * a.nz > maxp) maxp = a.nx * a.nz;
+    if (a.nx * a.ny > maxp) maxp = a.nx * a.ny;
+    const size_t cube_bytes = (size_t)a.nx * aniso_pyz(a.ny, a.nz) * sizeof(T);
+    g = 1;
+    long best_num = 0, best_den = 1;
+    for (int c = 1; c <= 256; ++c) {
+        const int lanes = c * maxp;
+        const int rounded = ((lanes + 63) / 64) * 64;
+        if (rounded > ANISO_MAX_NT || c * cube_bytes > 40 * 1024) break;
+        if ((long)lanes * best_den >= best_num * rounded) {   // ties: the larger workgroup
+            g = c;
+            best_num = lanes;
+            best_den = rounded;
+        }
+    }
+    nt = ((g * maxp + 63) / 64) * 64;                              // at most 256
+    lds = g * cube_bytes;                                          // at most 40 KB (34 KB for g = 1)
 }
 
 template <typename T, int MAXN>
 hipError_t launch_bound(const AnisoArgs &a)
 {
-    const size_t lds = (size_t)a.nx * a.ny * a.nz * sizeof(T);     // at most 32 KB
-    int pencils = a.ny * a.nz;
-    if (a.nx * a.nz > pencils) pencils = a.nx * a.nz;
-    if (a.nx * a.ny > pencils) pencils = a.nx * a.ny;
-    const int nt = ((pencils + 63) / 64) * 64;                     // at most 256
-    hipLaunchKernelGGL((ihelm_generic_kernel<T, MAXN>), dim3((unsigned)a.num_elems), dim3(nt), lds,
-                       a.stream, (const T *)a.u, (const T *)a.sx, (const T *)a.sy,
-                       (const T *)a.sz, (const T *)a.d, (T *)a.v, a.nx, a.ny, a.nz, a.num_elems);
+    int g, nt;
+    size_t lds;
+    aniso_shape<T>(a, g, nt, lds);
+    const long long groups = (a.num_elems + g - 1) / g;
+    hipLaunchKernelGGL((ihelm_aniso_kernel<T, MAXN, ANISO_HINT, ANISO_XCD>),
+                       dim3((unsigned)pencil_grid<ANISO_XCD>(groups)), dim3(nt), lds, a.stream,
+                       (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
+                       (const T *)a.d, (T *)a.v, a.nx, a.ny, a.nz, g, a.num_elems, groups);
     return hipGetLastError();
 }
 

@@ -1,5 +1,6 @@
-"""GPU parity of the operator on anisotropic elements (tpo_ihelm_apply_aniso, the generic
-runtime-size kernel) against the CPU oracle.  Bar as for the cubic operator."""
+"""GPU parity of the operator on anisotropic elements (tpo_ihelm_apply_aniso, the kernel with
+runtime sizes) against the CPU oracle.  Bar as for the cubic operator.  The batch sizes leave a
+ragged last workgroup for every number of elements per workgroup."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +13,8 @@ from paper_2604_19906_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 SHAPES = [(1, 1, 2), (2, 1, 1), (2, 3, 4), (4, 3, 2), (5, 5, 7), (7, 5, 5), (3, 16, 2), (16, 1, 16),
-          (8, 12, 10), (11, 13, 9), (16, 16, 15), (15, 16, 16), (16, 15, 16), (6, 6, 16)]
+          (8, 12, 10), (11, 13, 9), (16, 16, 15), (15, 16, 16), (16, 15, 16), (6, 6, 16),
+          (4, 4, 5), (9, 8, 8), (12, 12, 13), (13, 12, 12), (1, 16, 16), (16, 16, 1), (11, 11, 12)]
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -36,7 +38,7 @@ def aniso_inputs(dims, e, dtype, seed):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("dims", SHAPES)
 def test_aniso_shapes(dims, dtype):
-    for e in (1, 37):
+    for e in (1, 37, 203):
         u, sx, sy, sz, d = aniso_inputs(dims, e, dtype, 100 * dims[0] + 10 * dims[1] + dims[2])
         print(f"case aniso dims={dims} {dtype} E={e}", flush=True)
         got = tpo.apply_aniso_tensors(*map(dev, (u, sx, sy, sz, d)))
