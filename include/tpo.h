@@ -168,7 +168,7 @@ int tpo_ihelm_sep_has_variant(int n, int dtype, int variant);
  * [num_elems][n_x][n_y][n_z] C-contiguous, S_x is [n_x][n_x], S_y [n_y][n_y], S_z [n_z][n_z].
  * With n_x == n_y == n_z the call is tpo_ihelm_apply; every other shape runs one kernel with
  * runtime sizes whose mode products are compiled for every size of their own axis (measured
- * 3.7 - 6.4 TB/s of algorithmic traffic, against 5.0 - 5.8 of the tuned cubic kernels).
+ * 3.8 - 6.1 TB/s of algorithmic traffic, against 5.0 - 5.8 of the tuned cubic kernels).
  * Everything else (alignment, aliasing, ownership, stream, error order) as in tpo_ihelm_apply.
  */
 int tpo_ihelm_apply_aniso(const void *u, const void *S_x, const void *S_y, const void *S_z,
