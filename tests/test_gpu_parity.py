@@ -280,3 +280,58 @@ def test_graph_capture_and_replay():
         assert torch.equal(tv, eager), f"replay {rep}"
         ref = oracle.ihelm_apply(new_u, sx, sy, sz, d)
         assert oracle.max_rel_err_per_element(tv.cpu().numpy(), ref) <= 1e-12
+
+
+def test_graph_with_every_entry_point():
+    # the other entry points enqueue one kernel each in the same way: one graph holding the
+    # separable form, a forward transform, the convection term and an anisotropic call, replayed
+    # on changed inputs, each replay equal to the eager results
+    w = wl.custom(9, 150, "f64", key=1310, distinct_s=True)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    lam = wl.sep_inputs(w, 0, w.num_elems)
+    cw = wl.conv_custom(9, 60, "f64", key=1311)
+    cp, cm, cd, ci = wl.conv_inputs(cw)
+    rng = np.random.default_rng(6)
+    dims = (9, 7, 10)
+    mats = [wl.orthogonal_matrix(k, rng) for k in dims]
+    ua = rng.uniform(-1, 1, (90, *dims))
+    da = rng.uniform(0.03, 3.3, (90, *dims))
+    tu, tsx, tsy, tsz = map(dev, (u, sx, sy, sz))
+    tl = list(map(dev, lam))
+    tc = list(map(dev, (cp, cm, cd, ci)))
+    ta = [dev(ua)] + list(map(dev, mats)) + [dev(da)]
+    out_sep, out_fwd, out_an = torch.empty_like(tu), torch.empty_like(tu), torch.empty_like(ta[0])
+    out_conv = torch.empty_like(tc[0][0])
+
+    def enqueue(o_sep, o_fwd, o_conv, o_an):
+        tpo.apply_sep_tensors(tu, tsx, tsy, tsz, *tl, v=o_sep)
+        tpo.transform_tensors(tu, tsx, tsy, tsz, tpo.TPO_FORWARD, t=o_fwd)
+        tpo.convection_tensors(*tc, F=o_conv)
+        tpo.apply_aniso_tensors(*ta, v=o_an)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(out_sep, out_fwd, out_conv, out_an)             # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue(out_sep, out_fwd, out_conv, out_an)
+    for rep in range(3):
+        tu.copy_(torch.from_numpy(rng.uniform(-1, 1, u.shape)))
+        tc[0].copy_(torch.from_numpy(rng.uniform(-1, 1, cp.shape)))
+        ta[0].copy_(torch.from_numpy(rng.uniform(-1, 1, ua.shape)))
+        for o in (out_sep, out_fwd, out_conv, out_an):
+            o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = [torch.empty_like(o) for o in (out_sep, out_fwd, out_conv, out_an)]
+        enqueue(*eager)
+        torch.cuda.synchronize()
+        for name, got, want in zip(("sep", "forward", "convection", "aniso"),
+                                   (out_sep, out_fwd, out_conv, out_an), eager):
+            assert torch.equal(got, want), f"replay {rep}: {name}"
+    ref = oracle.ihelm_apply_aniso(ta[0].cpu().numpy(), *mats, da)
+    assert oracle.max_rel_err_per_element(out_an.cpu().numpy(), ref) <= 1e-12
