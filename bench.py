@@ -56,6 +56,7 @@ KERNEL_SOURCES = {
                         "tpo_pencil_f32.hip", "tpo_pencil_mm_f32.hip"],
     "transform": _COMMON + ["tpo_transform.hpp", "tpo_transform_f64.hip", "tpo_transform_f32.hip"],
     "convection": _COMMON + ["tpo_convection.hpp", "tpo_convection_f64.hip", "tpo_convection_f32.hip"],
+    "aniso": ["tpo_internal.h", "tpo_pencil.hpp", "tpo_generic.hip"],
 }
 
 
@@ -189,6 +190,118 @@ def bench_convection(args, torch, tpo, wl) -> int:
     return 0
 
 
+def bench_aniso(args, torch, tpo, wl) -> int:
+    """The operator on anisotropic elements (n_x, n_y, n_z points along the three axes) on one of
+    its synthetic configurations: same timing scheme, 3 * n_x * n_y * n_z words per element."""
+    import oracle
+
+    if args.variant != "auto":
+        log("bench.py: anisotropic elements have one kernel family; --variant does not apply")
+        return 2
+    w = wl.ANISO_CONFIGS[args.workload if args.workload < len(wl.ANISO_CONFIGS) else 2]
+    if args.elems:
+        w = wl.AnisoWorkload(w.name + f"_E{args.elems}", w.index, w.dtype, w.dims, args.elems)
+    dt = tpo.TPO_F64 if w.dtype == "f64" else tpo.TPO_F32
+    t0 = time.time()
+    tu, tsx, tsy, tsz, td = wl.aniso_to_device(w)
+    tv = torch.empty_like(tu)
+    torch.cuda.synchronize()
+    alg_bytes = w.bytes_per_elem * w.num_elems
+    alg_flop = w.flop_per_elem * w.num_elems
+    log(f"[bench] {w.name} (aniso): inputs resident after {time.time() - t0:.1f}s "
+        f"({alg_bytes / 1e9:.2f} GB for u, D, v)")
+    stream = torch.cuda.current_stream()
+    ptrs = (tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(), td.data_ptr(),
+            tv.data_ptr())
+
+    def step():
+        rc = tpo.tpo_ihelm_apply_aniso(*ptrs, *w.dims, w.num_elems, dt, stream.cuda_stream)
+        if rc != tpo.TPO_OK:
+            raise tpo.TpoError(rc, "tpo_ihelm_apply_aniso")
+
+    for _ in range(args.warmup):
+        step()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    kernel_ms = [a.elapsed_time(b) for a, b in evs]
+    avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    achieved_gbs = alg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    achieved_tflops = alg_flop / (avg_kernel_ms * 1e-3) / 1e12
+    log(f"[bench] kernel avg {avg_kernel_ms:.4f} ms (min {min(kernel_ms):.4f}, max "
+        f"{max(kernel_ms):.4f}); wall/step {ms_per_step:.4f} ms; {achieved_gbs:.0f} GB/s; "
+        f"{achieved_tflops:.2f} TFLOP/s")
+
+    # streaming ceiling and counter calibration: v = u .* D over the same three fields
+    def stream_step():
+        rc = tpo.tpo_stream_scale(ptrs[0], ptrs[4], ptrs[5], tu.numel(), dt, stream.cuda_stream)
+        if rc != tpo.TPO_OK:
+            raise tpo.TpoError(rc, "tpo_stream_scale")
+
+    for _ in range(3):
+        stream_step()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(10):
+        stream_step()
+    b.record(stream)
+    torch.cuda.synchronize()
+    stream_gbs = alg_bytes / (a.elapsed_time(b) / 10 * 1e-3) / 1e9
+    log(f"[bench] streaming ceiling v=u.*D: {stream_gbs:.0f} GB/s")
+
+    step()
+    torch.cuda.synchronize()
+    hi = min(64, w.num_elems)
+    ref = oracle.ihelm_apply_aniso(*wl.aniso_inputs(w, 0, hi))
+    err = oracle.max_rel_err_per_element(tv[:hi].cpu().numpy(), ref)
+    tol = 1e-12 if w.dtype == "f64" else 2e-5
+    if not err <= tol:
+        log(f"[bench] PARITY FAILURE on the timed output: {err:.3e} > {tol}")
+        return 1
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        ns = min(16384, w.num_elems)
+        hin = wl.aniso_inputs(w, 0, ns)
+        oracle.ihelm_apply_aniso(hin[0][:64], *hin[1:4], hin[4][:64])        # load + warm
+        rate, passes, cpu_s = timed_passes(lambda: oracle.ihelm_apply_aniso(*hin), ns, 1)
+        cpu = {"value": rate, "unit": "elements/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {ns} elements of {w.name}, {passes} pass(es), 1 host thread "
+                         f"({cpu_s:.2f} s wall)"}
+        log(f"[bench] CPU oracle baseline: {rate:.0f} elements/s on 1 thread")
+
+    out = {
+        "metric": "elements/s + GFLOP/s and % of binding roofline, anisotropic TPO apply",
+        "value": w.num_elems / (ms_per_step * 1e-3), "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "op": "aniso", "dims": list(w.dims),
+                   "num_elems": w.num_elems, "layout": "[E,n_x,n_y,n_z] element-contiguous",
+                   "parallelism": "1 GPU"},
+        "gflops": alg_flop / (ms_per_step * 1e-3) / 1e9,
+        "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": min(kernel_ms),
+        "fp_frac_of_peak": achieved_tflops / FP_PEAK_TFLOPS[w.dtype],
+        "stream_ceiling_gbs": stream_gbs,
+        "parity_max_rel_err_sample": err,
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": stored_traffic(w.name + ":aniso", "aniso", "aniso")},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    tpo.tpo_destroy()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -196,11 +309,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the named configurations")
     ap.add_argument("--variant", default="auto", choices=["auto", "pencil", "mfma", "pencil_mm"])
-    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep", "forward", "backward", "convection"],
+    ap.add_argument("--op", default="ihelm", choices=["ihelm", "ihelm_sep", "forward", "backward", "convection", "aniso"],
                     help="ihelm: D read from HBM (the headline); ihelm_sep: D evaluated in the "
                          "kernel from lam_x, lam_y, lam_z, mu (two HBM streams instead of three); "
                          "forward / backward: one half of the operator on its own; convection: the "
-                         "convection volume term (--workload indexes its own configurations)")
+                         "convection volume term; aniso: the operator on anisotropic elements "
+                         "(--workload indexes the configurations of these two on their own)")
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=262144,
@@ -227,6 +341,8 @@ def main() -> int:
 
     if args.op == "convection":
         return bench_convection(args, torch, tpo, wl)
+    if args.op == "aniso":
+        return bench_aniso(args, torch, tpo, wl)
 
     w = wl.CONFIGS[args.workload]
     if args.elems:

@@ -27,10 +27,11 @@ namespace tpo {
 namespace {
 
 constexpr int ANISO_MAX_NT = 256;
-// Non-temporal loads of u_e and stores of v_e, workgroups renumbered per die: the best or within
-// 2 % of the best of a sweep over eight shapes on MI355X (hint bits x renumbering x elements
-// per workgroup x LDS floor).
-constexpr int ANISO_HINT = 3;
+// Non-temporal stores of v_e, workgroups renumbered per die: the best or within 2 % of the best
+// of a sweep over eight shapes on MI355X (hint bits x renumbering x elements per workgroup x LDS
+// floor).  Non-temporal loads of u_e as well measured the same rate on average with 5 % more
+// HBM reads (the 32-byte pieces two rows of a pass share are then fetched twice).
+constexpr int ANISO_HINT = 2;
 constexpr bool ANISO_XCD = true;
 
 // f(integral_constant<int, n>) for the runtime n in 1 .. MAXN (uniform over the workgroup).

@@ -376,3 +376,120 @@ def conv_to_device(w: ConvWorkload, threads: int = 12, chunk: int = 4 * CONV_BLO
     d_vq, i_vq = conv_matrices(w)
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     return tp, tm, up(d_vq), up(i_vq)
+
+
+# ------------------------------------------------------------------------------------------
+# Inputs of the operator on anisotropic elements: the recipe of the cubic workloads with one
+# size per axis (an orthogonal matrix and an eigenvalue vector per direction, a shift per
+# element, uniform u).  Shapes stand for extruded meshes (a different order along one axis).
+
+@dataclass(frozen=True)
+class AnisoWorkload:
+    """One synthetic configuration of the operator with ``dims = (n_x, n_y, n_z)`` points."""
+
+    name: str
+    index: int          # seed key, disjoint from the other configurations
+    dtype: str
+    dims: Tuple[int, int, int]
+    num_elems: int
+
+    @property
+    def np_dtype(self):
+        return np.float64 if self.dtype == "f64" else np.float32
+
+    @property
+    def word(self) -> int:
+        return 8 if self.dtype == "f64" else 4
+
+    @property
+    def points(self) -> int:
+        return self.dims[0] * self.dims[1] * self.dims[2]
+
+    @property
+    def bytes_per_elem(self) -> int:
+        """Algorithmic traffic per element: u_e and D_e in, v_e out."""
+        return 3 * self.points * self.word
+
+    @property
+    def flop_per_elem(self) -> int:
+        """Six mode products (2 n_axis flops per point each) and the scale."""
+        return self.points * (4 * sum(self.dims) + 1)
+
+
+ANISO_CONFIGS = (
+    AnisoWorkload("aniso0_f64_5x6x7_E512", 30, "f64", (5, 6, 7), 512),
+    AnisoWorkload("aniso1_f64_8x8x12_E131072", 31, "f64", (8, 8, 12), 131072),
+    AnisoWorkload("aniso2_f64_11x11x14_E131072", 32, "f64", (11, 11, 14), 131072),
+    AnisoWorkload("aniso3_f32_12x12x16_E262144", 33, "f32", (12, 12, 16), 262144),
+)
+
+_STREAM_AS, _STREAM_AL, _STREAM_AM, _STREAM_AU = 7, 8, 9, 10
+
+
+def aniso_custom(dims, num_elems: int, dtype: str = "f64", key: int = 130) -> AnisoWorkload:
+    dims = tuple(int(k) for k in dims)
+    return AnisoWorkload(f"aniso_custom_{dtype}_{dims[0]}x{dims[1]}x{dims[2]}_E{num_elems}", key,
+                         dtype, dims, num_elems)
+
+
+def aniso_matrices(w: AnisoWorkload):
+    """``(S_x, S_y, S_z)``: one orthogonal matrix per axis, ``[n_axis, n_axis]``."""
+    rng = _rng(w.index, _STREAM_AS)
+    return tuple(orthogonal_matrix(k, rng).astype(w.np_dtype) for k in w.dims)
+
+
+def aniso_field_u(w: AnisoWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """``u[start:stop]`` of shape ``[stop-start, n_x, n_y, n_z]``, U(-1, 1), drawn in fp64 per
+    seed block and rounded once."""
+    stop = w.num_elems if stop is None else stop
+    out = np.empty((stop - start, *w.dims), dtype=w.np_dtype)
+    for b, lo, hi in _blocks(start, stop):
+        cnt = hi - b * BLOCK
+        blk = _rng(w.index, _STREAM_AU, b).uniform(-1.0, 1.0, (cnt, *w.dims))
+        out[lo - start:hi - start] = blk[lo - b * BLOCK:]
+    return out
+
+
+def aniso_diagonal_d(w: AnisoWorkload, start: int = 0, stop: int | None = None) -> np.ndarray:
+    """``D[e,i,j,k] = 1 / (lam_x[i] + lam_y[j] + lam_z[k] + mu_e)`` with ``lam`` ~ U(0.1, 10)
+    per axis and ``mu_e`` ~ U(0, 1), evaluated in fp64 and rounded once (an input recipe)."""
+    stop = w.num_elems if stop is None else stop
+    rng = _rng(w.index, _STREAM_AL)
+    lx, ly, lz = (rng.uniform(0.1, 10.0, k) for k in w.dims)
+    lam3 = lx[:, None, None] + ly[None, :, None] + lz[None, None, :]
+    out = np.empty((stop - start, *w.dims), dtype=w.np_dtype)
+    for b, lo, hi in _blocks(start, stop):
+        mu = _rng(w.index, _STREAM_AM, b).uniform(0.0, 1.0, BLOCK)[lo - b * BLOCK:hi - b * BLOCK]
+        out[lo - start:hi - start] = 1.0 / (lam3[None] + mu[:, None, None, None])
+    return out
+
+
+def aniso_inputs(w: AnisoWorkload, start: int = 0, stop: int | None = None):
+    """``(u, S_x, S_y, S_z, D)`` for elements ``start..stop-1`` as host arrays."""
+    sx, sy, sz = aniso_matrices(w)
+    return aniso_field_u(w, start, stop), sx, sy, sz, aniso_diagonal_d(w, start, stop)
+
+
+def aniso_to_device(w: AnisoWorkload, threads: int = 12, chunk: int = 2 * BLOCK):
+    """Device tensors ``(u, S_x, S_y, S_z, D)`` of a whole anisotropic workload, generated
+    block by block on the host and copied into place."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import torch
+
+    e = w.num_elems
+    tdtype = torch.float64 if w.dtype == "f64" else torch.float32
+    tu = torch.empty((e, *w.dims), dtype=tdtype, device="cuda")
+    td = torch.empty((e, *w.dims), dtype=tdtype, device="cuda")
+    spans = [(lo, min(e, lo + chunk)) for lo in range(0, e, chunk)]
+
+    def gen(span):
+        lo, hi = span
+        return lo, hi, aniso_field_u(w, lo, hi), aniso_diagonal_d(w, lo, hi)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for lo, hi, hu, hd in ex.map(gen, spans):
+            tu[lo:hi].copy_(torch.from_numpy(hu))
+            td[lo:hi].copy_(torch.from_numpy(hd))
+    mats = tuple(torch.from_numpy(np.ascontiguousarray(s)).cuda() for s in aniso_matrices(w))
+    return (tu, *mats, td)

@@ -83,3 +83,21 @@ def test_convection_inputs():
     assert m.min() >= 0.5 and m.max() <= 2.0 and np.abs(p).max() <= 1.0
     assert not np.array_equal(p[0, 0], p[0, 1]) and not np.array_equal(p[0, 0], p[1, 0])
     assert wl.conv_inputs(wl.conv_custom(4, 3, "f32"))[0].dtype == np.float32
+
+
+def test_anisotropic_inputs():
+    w = wl.ANISO_CONFIGS[0]
+    u, sx, sy, sz, d = wl.aniso_inputs(w)
+    assert u.shape == d.shape == (w.num_elems, *w.dims)
+    for s, k in zip((sx, sy, sz), w.dims):
+        assert s.shape == (k, k)
+        assert np.allclose(s.T @ s, np.eye(k), atol=1e-13)
+        assert not np.allclose(s, s.T)
+    assert d.min() > 1 / 31.0 - 1e-12 and d.max() < 1 / 0.3
+    assert np.abs(u).max() <= 1.0
+    # any range of elements can be regenerated on its own, across seed blocks
+    big = wl.aniso_custom((3, 4, 5), 9000, "f32", key=131)
+    assert np.array_equal(wl.aniso_field_u(big, 4000, 4200), wl.aniso_field_u(big)[4000:4200])
+    assert np.array_equal(wl.aniso_diagonal_d(big, 4000, 4200), wl.aniso_diagonal_d(big)[4000:4200])
+    assert wl.aniso_field_u(big).dtype == np.float32
+    assert w.bytes_per_elem == 3 * 5 * 6 * 7 * 8 and w.flop_per_elem == 210 * (4 * 18 + 1)
