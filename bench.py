@@ -322,7 +322,7 @@ def main() -> int:
     args = ap.parse_args()
 
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU; elements are independent, so a multi-GPU "
+        log("bench.py: the library runs on ONE GPU; elements are independent, so a multi-GPU "
             "run would be a contiguous split of the element range with no exchange. "
             "Run with --gpus 1.")
         return 2
