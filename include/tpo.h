@@ -31,9 +31,12 @@ typedef enum {
     TPO_OK = 0,
     TPO_ERR_INVALID_ARG = -1,      /* NULL pointer with num_elems > 0, n < 1, num_elems < 0,
                                       unknown dtype or variant, misaligned pointer */
-    TPO_ERR_UNSUPPORTED = -2,      /* n > TPO_MAX_N, or a variant that has no kernel for (n, dtype) */
+    TPO_ERR_UNSUPPORTED = -2,      /* n > TPO_MAX_N, a variant that has no kernel for (n, dtype), or a
+                                      batch that needs more than 2^31-1 workgroups in one launch */
     TPO_ERR_NOT_INITIALIZED = -3,  /* tpo_create has not succeeded on the current device */
-    TPO_ERR_DEVICE = -4,           /* no gfx950 device, or the launch was rejected by HIP */
+    TPO_ERR_DEVICE = -4,           /* no gfx950 device, or THIS launch was rejected by HIP (an error
+                                      left recorded by the caller's earlier HIP calls is dropped
+                                      before the launch and never reported here) */
     TPO_ERR_ALIAS = -5             /* v overlaps an input other than "v == u exactly" */
 } tpo_status_t;
 
@@ -192,11 +195,16 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
 
 /*
  * tpo_convection_apply -- volume integral of the convective flux, Eq. 1 of the paper (the
- * `convection` kernel of its Tables 1 and 2), in the index form the paper prints for its DSL:
+ * `convection` kernel of its Tables 1 and 2).  Per velocity component c and element e it is the
+ * sum over the three flux directions d of a tensor-product operator applied to the
+ * metric-weighted flux of that direction: the differentiation matrix acts along direction d, the
+ * interpolation matrix along the other two.  With the cube axes numbered from the fastest one
+ * (axis 0 = last array index, direction d = 0 is xi):
  *
- *   F[c,e,k,j,i] = sum_l sum_m sum_n (  D_vq[i,l] I_vq[j,m] I_vq[k,n] M[e,n,m,l] P[c,0,e,n,m,l]
- *                                     + I_vq[i,l] D_vq[j,m] I_vq[k,n] M[e,n,m,l] P[c,1,e,n,m,l]
- *                                     + I_vq[i,l] I_vq[j,m] D_vq[k,n] M[e,n,m,l] P[c,2,e,n,m,l] )
+ *   F[c,e] = sum_{d=0,1,2}  ( A(d,2) (x) A(d,1) (x) A(d,0) )  ( M[e] .* P[c,d,e] ),
+ *   A(d,a) = D_vq if a == d, else I_vq,
+ *
+ * each factor A[x,q] contracting the quadrature index q of its axis.
  *
  *   P      DEVICE pointer, read only, [3][3][num_elems][n_q][n_q][n_q] C-contiguous: velocity
  *          component c, flux direction (xi, eta, zeta), element, quadrature point (last index fastest)

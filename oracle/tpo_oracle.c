@@ -316,19 +316,24 @@ int tpo_oracle_ihelm_aniso(const double *u, const double *Sx, const double *Sy, 
 }
 
 /* ------------------------------------------------------------------------------------------
- * Volume integral of the convective flux (Eq. 1 of the paper; its index form is the one the
- * paper prints for its DSL):
+ * Volume integral of the convective flux (Eq. 1 of the paper).  Per component c and element e
+ * it is the sum over the three flux directions d of a tensor-product operator applied to the
+ * metric-weighted flux of that direction, with the differentiation matrix along direction d and
+ * the interpolation matrix along the other two:
  *
- *   F[c,e,k,j,i] = sum_l sum_m sum_n (  Dm[i,l] * Im[j,m] * Im[k,n] * M[e,n,m,l] * P[c,0,e,n,m,l]
- *                                     + Im[i,l] * Dm[j,m] * Im[k,n] * M[e,n,m,l] * P[c,1,e,n,m,l]
- *                                     + Im[i,l] * Im[j,m] * Dm[k,n] * M[e,n,m,l] * P[c,2,e,n,m,l] )
+ *   F[c,e] = sum_{d=0,1,2}  ( A(d,2) (x) A(d,1) (x) A(d,0) )  ( M[e] .* P[c,d,e] ),
+ *   A(d,a) = Dm if a == d, else Im.
+ *
+ * Cube axes are numbered from the FASTEST one: axis 0 is the last array index.  Written out,
+ *   term_d[x2,x1,x0] = sum_{q2,q1,q0} A(d,2)[x2,q2] A(d,1)[x1,q1] A(d,0)[x0,q0] (M.*P_d)[q2,q1,q0].
  *
  * Dm, Im: [nv][nq] row-major (differentiation and interpolation from the nq quadrature points
  * to the nv nodes of one direction); M: [E][nq][nq][nq]; P: [3][3][E][nq][nq][nq] (component c,
- * direction, element); F: [3][E][nv][nv][nv].  The last cube axis (i, l) is the fastest.
+ * direction d, element); F: [3][E][nv][nv][nv].
  *
- * _direct: the six-deep sums as written.  _lifted: each term as three successive one-dimensional
- * products (Sec. 2.2), innermost axis first, the three terms added at the end. */
+ * _direct: each direction's six-deep sum on its own, the three results added in the order
+ * d = 0, 1, 2.  _lifted: each term as three successive one-dimensional products (Sec. 2.2),
+ * fastest axis first, the three terms added at the end. */
 int tpo_oracle_convection_direct(const double *P, const double *M, const double *Dm,
                                  const double *Im, double *F, int nv, int nq, long long num_elems)
 {
@@ -339,24 +344,26 @@ int tpo_oracle_convection_direct(const double *P, const double *M, const double 
     for (int c = 0; c < 3; ++c)
         for (long long e = 0; e < num_elems; ++e) {
             const double *Me = M + (size_t)e * qc;
-            const double *P0 = P + (((size_t)c * 3 + 0) * num_elems + e) * qc;
-            const double *P1 = P + (((size_t)c * 3 + 1) * num_elems + e) * qc;
-            const double *P2 = P + (((size_t)c * 3 + 2) * num_elems + e) * qc;
             double *Fe = F + ((size_t)c * num_elems + e) * vc;
-            for (int k = 0; k < nv; ++k)
-                for (int j = 0; j < nv; ++j)
-                    for (int i = 0; i < nv; ++i) {
-                        double acc = 0.0;
-                        for (int l = 0; l < nq; ++l)
-                            for (int m = 0; m < nq; ++m)
-                                for (int n = 0; n < nq; ++n) {
-                                    const size_t x = ((size_t)n * nq + m) * nq + l;
-                                    acc = acc + Dm[i * nq + l] * Im[j * nq + m] * Im[k * nq + n] * Me[x] * P0[x]
-                                              + Im[i * nq + l] * Dm[j * nq + m] * Im[k * nq + n] * Me[x] * P1[x]
-                                              + Im[i * nq + l] * Im[j * nq + m] * Dm[k * nq + n] * Me[x] * P2[x];
-                                }
-                        Fe[((size_t)k * nv + j) * nv + i] = acc;
-                    }
+            for (size_t x = 0; x < vc; ++x) Fe[x] = 0.0;
+            for (int d = 0; d < 3; ++d) {
+                const double *Pd = P + (((size_t)c * 3 + d) * num_elems + e) * qc;
+                const double *A[3];                    /* operator along axis 0, 1, 2 */
+                for (int a = 0; a < 3; ++a) A[a] = (a == d) ? Dm : Im;
+                for (int x2 = 0; x2 < nv; ++x2)
+                    for (int x1 = 0; x1 < nv; ++x1)
+                        for (int x0 = 0; x0 < nv; ++x0) {
+                            double term = 0.0;
+                            for (int q2 = 0; q2 < nq; ++q2)
+                                for (int q1 = 0; q1 < nq; ++q1)
+                                    for (int q0 = 0; q0 < nq; ++q0) {
+                                        const size_t q = ((size_t)q2 * nq + q1) * nq + q0;
+                                        term = term + A[2][x2 * nq + q2] * A[1][x1 * nq + q1]
+                                                      * A[0][x0 * nq + q0] * (Me[q] * Pd[q]);
+                                    }
+                            Fe[((size_t)x2 * nv + x1) * nv + x0] += term;
+                        }
+            }
         }
     return 0;
 }

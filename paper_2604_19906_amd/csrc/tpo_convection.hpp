@@ -1,10 +1,11 @@
-// Volume integral of the convective flux (Eq. 1 of the paper, printed in index form for the
-// paper's DSL):
+// Volume integral of the convective flux (Eq. 1 of the paper).  Per component c and element e:
+// the sum over the three flux directions d of a tensor-product operator on the metric-weighted
+// flux of that direction, the differentiation matrix D along direction d and the interpolation
+// matrix I along the other two.  Cube axes are called l (fastest), m, n below; direction 0 is l:
 //
-//   F[c,e,k,j,i] = sum_l sum_m sum_n (  D[i,l] I[j,m] I[k,n] M[e,n,m,l] P[c,0,e,n,m,l]
-//                                     + I[i,l] D[j,m] I[k,n] M[e,n,m,l] P[c,1,e,n,m,l]
-//                                     + I[i,l] I[j,m] D[k,n] M[e,n,m,l] P[c,2,e,n,m,l] )
+//   F[c,e] = (I (x) I (x) D) (M.P0) + (I (x) D (x) I) (M.P1) + (D (x) I (x) I) (M.P2),
 //
+// the three factors of a Kronecker product acting on axes n, m, l in that order.  Written here
 // for square D, I (as many nodes as quadrature points per direction).  Sum-factorised and with
 // the three terms merged as early as the algebra allows, eight mode products per (c, e) instead
 // of nine:
@@ -477,7 +478,8 @@ struct ConvectionRectLauncher {
     static hipError_t launch(const ConvectionArgs &a)
     {
         const long long blocks = convection_grid<XCD>((3 * a.num_elems + G - 1) / G);
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return kGridTooLarge;
+        drop_stale_error();
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.p, (const T *)a.m, (const T *)a.d_vq, (const T *)a.i_vq,
                            (T *)a.f, a.num_elems);
@@ -525,7 +527,8 @@ struct ConvectionLauncher {
     static hipError_t launch(const ConvectionArgs &a)
     {
         const long long blocks = convection_grid<XCD>((3 * a.num_elems + G - 1) / G);
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return kGridTooLarge;
+        drop_stale_error();
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.p, (const T *)a.m, (const T *)a.d_vq, (const T *)a.i_vq,
                            (T *)a.f, a.num_elems);
