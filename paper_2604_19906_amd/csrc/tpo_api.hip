@@ -42,6 +42,14 @@ const tpo::KernelEntry *lookup(int n, int dtype, int variant)
     return nullptr;
 }
 
+// Status of an entry point from what its launcher returned.
+int launch_status(hipError_t err)
+{
+    if (err == hipSuccess) return TPO_OK;
+    (void)hipGetLastError();
+    return err == tpo::kGridTooLarge ? TPO_ERR_UNSUPPORTED : TPO_ERR_DEVICE;
+}
+
 // True when tpo_create has succeeded (and not been undone) on the calling thread's device.
 bool created_on_current_device()
 {
@@ -155,11 +163,7 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
 
     if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ApplyArgs a{u, S_x, S_y, S_z, D, v, num_elems, (hipStream_t)stream};
-    if (k->launch(a) != hipSuccess) {
-        (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
-    }
-    return TPO_OK;
+    return launch_status(k->launch(a));
 }
 
 int tpo_convection_has_shape(int n_v, int n_q, int dtype)
@@ -182,11 +186,7 @@ int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const v
 
     if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ConvectionArgs a{P, M, D_vq, I_vq, F, num_elems, (hipStream_t)stream};
-    if (k->launch(a) != hipSuccess) {
-        (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
-    }
-    return TPO_OK;
+    return launch_status(k->launch(a));
 }
 
 int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const void *S_z, void *t,
@@ -200,12 +200,7 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
 
     if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::TransformArgs a{u, S_x, S_y, S_z, t, num_elems, (hipStream_t)stream};
-    const hipError_t err = direction == TPO_FORWARD ? k->launch_forward(a) : k->launch_backward(a);
-    if (err != hipSuccess) {
-        (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
-    }
-    return TPO_OK;
+    return launch_status(direction == TPO_FORWARD ? k->launch_forward(a) : k->launch_backward(a));
 }
 
 int tpo_ihelm_sep_variant_for(int n, int dtype)
@@ -247,11 +242,7 @@ int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y,
     if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::ApplyArgs a{u, S_x, S_y, S_z, nullptr, v, num_elems, (hipStream_t)stream,
                      lam_x, lam_y, lam_z, mu};
-    if (k->launch_sep(a) != hipSuccess) {
-        (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
-    }
-    return TPO_OK;
+    return launch_status(k->launch_sep(a));
 }
 
 int tpo_ihelm_apply_sep(const void *u, const void *S_x, const void *S_y, const void *S_z,
@@ -274,11 +265,7 @@ int tpo_ihelm_apply_aniso(const void *u, const void *S_x, const void *S_y, const
     if (num_elems == 0) return TPO_OK;
     if (!created_on_current_device()) return TPO_ERR_NOT_INITIALIZED;
     tpo::AnisoArgs a{u, S_x, S_y, S_z, D, v, n_x, n_y, n_z, num_elems, (hipStream_t)stream};
-    if (tpo::launch_ihelm_generic(a, dtype) != hipSuccess) {
-        (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
-    }
-    return TPO_OK;
+    return launch_status(tpo::launch_ihelm_generic(a, dtype));
 }
 
 int tpo_ihelm_apply(const void *u, const void *S_x, const void *S_y, const void *S_z,

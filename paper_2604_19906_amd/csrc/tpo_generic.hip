@@ -211,6 +211,7 @@ hipError_t launch_bound(const AnisoArgs &a)
     size_t lds;
     aniso_shape<T>(a, g, nt, lds);
     const long long groups = (a.num_elems + g - 1) / g;
+    drop_stale_error();
     hipLaunchKernelGGL((ihelm_aniso_kernel<T, MAXN, ANISO_HINT, ANISO_XCD>),
                        dim3((unsigned)pencil_grid<ANISO_XCD>(groups)), dim3(nt), lds, a.stream,
                        (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
@@ -221,7 +222,7 @@ hipError_t launch_bound(const AnisoArgs &a)
 template <typename T>
 hipError_t launch_generic(const AnisoArgs &a)
 {
-    if (a.num_elems <= 0 || a.num_elems > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (a.num_elems <= 0 || a.num_elems > 0x7fffffffLL) return kGridTooLarge;
     int n = a.nx > a.ny ? a.nx : a.ny;
     if (a.nz > n) n = a.nz;
     if (n <= 4) return launch_bound<T, 4>(a);

@@ -6,6 +6,16 @@
 
 namespace tpo {
 
+// Returned by a launcher whose grid would pass the 2^31-1 workgroups of a HIP launch; the entry
+// points report it as TPO_ERR_UNSUPPORTED (the arguments are valid, the batch is too large
+// for one launch).
+constexpr hipError_t kGridTooLarge = hipErrorInvalidConfiguration;
+
+// Called right before a kernel launch: drops an error that an earlier runtime call of this
+// thread (the caller's, e.g. an event query that returned "not ready") left recorded, so that
+// the hipGetLastError() after the launch reports this launch only.
+inline void drop_stale_error() { (void)hipGetLastError(); }
+
 struct ApplyArgs {
     const void *u, *sx, *sy, *sz, *d;
     void *v;

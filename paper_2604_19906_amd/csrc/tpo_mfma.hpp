@@ -310,12 +310,13 @@ struct MfmaLauncher {
     static hipError_t launch_as(const ApplyArgs &a)
     {
         const long long nbatch = (a.num_elems + G - 1) / G;
-        if (nbatch <= 0 || nbatch > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (nbatch <= 0 || nbatch > 0x7fffffffLL) return kGridTooLarge;
         long long blocks = PERSIST ? nbatch : pencil_grid<XCD>(nbatch);
         if (PERSIST) {
             if (wgs_per_device[SAMES] <= 0) return hipErrorNotInitialized;
             if (blocks > wgs_per_device[SAMES]) blocks = wgs_per_device[SAMES];
         }
+        drop_stale_error();
         hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD>),
                            dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,

@@ -387,7 +387,8 @@ struct PencilLauncherT {
     static hipError_t launch(const ApplyArgs &a)
     {
         const long long blocks = pencil_grid<Tune::XCD>((a.num_elems + G - 1) / G);
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return kGridTooLarge;
+        drop_stale_error();
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (const T *)a.d, (T *)a.v, a.num_elems, (const T *)a.lam_x,

@@ -295,7 +295,8 @@ struct PencilMmLauncher {
     static hipError_t launch_as(const ApplyArgs &a)
     {
         const long long blocks = pencil_grid<Tune::XCD>((a.num_elems + G - 1) / G);
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return kGridTooLarge;
+        drop_stale_error();
         hipLaunchKernelGGL(kernel<SEP>(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const float *)a.u, (const float *)a.sx, (const float *)a.sy,
                            (const float *)a.sz, (const float *)a.d, (float *)a.v, a.num_elems,

@@ -7,6 +7,7 @@
 #include <cstdint>
 
 #include "tpo.h"
+#include "tpo_internal.h"
 
 namespace {
 
@@ -34,11 +35,13 @@ hipError_t launch(const void *u, const void *d, void *v, long long count, hipStr
     const size_t tail = (size_t)count - nvec * W;
     if (nvec) {
         const size_t blocks = (nvec + 255) / 256;
-        if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+        if (blocks > 0x7fffffffULL) return tpo::kGridTooLarge;
+        tpo::drop_stale_error();
         hipLaunchKernelGGL(stream_scale_kernel<V>, dim3((unsigned)blocks), dim3(256), 0, s,
                            (const V *)u, (const V *)d, (V *)v, nvec);
     }
     if (tail)
+        tpo::drop_stale_error();
         hipLaunchKernelGGL(stream_scale_kernel<T>, dim3(1), dim3(256), 0, s,
                            (const T *)u + nvec * W, (const T *)d + nvec * W,
                            (T *)v + nvec * W, tail);
@@ -61,7 +64,7 @@ extern "C" int tpo_stream_scale(const void *u, const void *D, void *v, long long
                              : launch<float, float4_>(u, D, v, count, (hipStream_t)stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        return TPO_ERR_DEVICE;
+        return e == tpo::kGridTooLarge ? TPO_ERR_UNSUPPORTED : TPO_ERR_DEVICE;
     }
     return TPO_OK;
 }

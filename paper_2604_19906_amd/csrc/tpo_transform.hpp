@@ -88,7 +88,8 @@ struct TransformLauncher {
     static hipError_t launch(const TransformArgs &a)
     {
         const long long blocks = pencil_grid<Tune::XCD>((a.num_elems + G - 1) / G);
-        if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (blocks <= 0 || blocks > 0x7fffffffLL) return kGridTooLarge;
+        drop_stale_error();
         hipLaunchKernelGGL(kernel(), dim3((unsigned)blocks), dim3(Sh::NT), LDS, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
                            (T *)a.t, a.num_elems);
