@@ -32,3 +32,40 @@ def run(u, sx, sy, sz, d, variant=tpo.TPO_VARIANT_AUTO, same_s_pointer=None):
 
 def upload_full(w):
     return wl.to_device(w)
+
+
+def oracle_every_element(num_elems, host_block, device_inputs, oracle_fn, outs, tol, label,
+                         block=16384, workers=6, oracle_in_pool=False):
+    """The oracle on EVERY element of a full-size workload, block by block.
+
+    ``host_block(lo, hi)`` draws the block's host inputs again from the seeds (oracle inputs are
+    never read back from the device); ``device_inputs(lo, hi)`` returns the device copies of the
+    per-element arrays among them, in the same order, and is only compared with them;
+    ``oracle_fn(*host inputs)`` is the CPU oracle; ``outs`` maps a name to a device result.
+    Blocks are drawn by a thread pool; the oracle runs in the calling thread (it has its own
+    OpenMP threads) unless ``oracle_in_pool`` (for its single-threaded functions).
+    Returns name -> worst max-norm relative error per element."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+
+    spans = [(lo, min(num_elems, lo + block)) for lo in range(0, num_elems, block)]
+    worst = {name: 0.0 for name in outs}
+
+    def work(span):
+        lo, hi = span
+        host = host_block(lo, hi)
+        return lo, hi, host, (oracle_fn(*host) if oracle_in_pool else None)
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        for lo, hi, host, ref in ex.map(work, spans):
+            for h, t in zip(host, device_inputs(lo, hi)):
+                if t is not None:
+                    assert np.array_equal(h, t.cpu().numpy()), f"{label}: inputs differ at {lo}"
+            if ref is None:
+                ref = oracle_fn(*host)
+            for name, tv in outs.items():
+                err = oracle.max_rel_err_per_element(tv[lo:hi].cpu().numpy(), ref)
+                assert err <= tol, f"{label} {name}: elements {lo}..{hi}: err {err:.3e}"
+                worst[name] = max(worst[name], err)
+    return worst

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import oracle
-from gpu_util import TOL, VARIANTS, dev, run, upload_full
+from gpu_util import TOL, VARIANTS, dev, oracle_every_element, run, upload_full
 from paper_2604_19906_amd import tpo
 from paper_2604_19906_amd import workloads as wl
 
@@ -80,57 +80,116 @@ def test_golden_file(repo_root):
         assert oracle.max_rel_err_per_element(got, want.reshape(got.shape)) <= 1e-12
 
 
-def sample_spans(e):
-    """First and last 512 elements plus eight seeded 256-element windows."""
-    rng = np.random.default_rng(12345 + e)
-    spans = [(0, min(512, e)), (max(0, e - 512), e)]
-    for s in rng.integers(0, max(1, e - 256), 8):
-        spans.append((int(s), int(min(e, s + 256))))
-    return spans
+def oracle_over_all_elements(w, tu, td, outs):
+    """Every element of workload ``w`` against the oracle (see gpu_util.oracle_every_element)."""
+    sx, sy, sz = wl.direction_matrices(w)
+    return oracle_every_element(
+        w.num_elems,
+        lambda lo, hi: (wl.field_u(w, lo, hi), sx, sy, sz, wl.diagonal_d(w, lo, hi)),
+        lambda lo, hi: (tu[lo:hi], None, None, None, td[lo:hi]),
+        oracle.ihelm_apply, outs, TOL[w.dtype], w.name)
 
 
-def torch_reference_chunk(u, sx, sy, sz, d):
-    """Independent full-coverage cross-check (library einsum on the device; not the oracle)."""
-    t = torch.einsum("li,mj,qk,elmq->eijk", sx, sy, sz, u)
-    return torch.einsum("il,jm,kq,elmq->eijk", sx, sy, sz, d * t)
-
-
-# the four large configurations at full size, in the launch configuration the benchmark uses
+# the four large configurations at full size, in the launch configuration the benchmark uses;
+# the oracle checks every element of every family's result
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
 def test_full_size_configs(idx):
     w = wl.CONFIGS[idx]
     print(f"case {w.name}: generating", flush=True)
     tu, tsx, tsy, tsz, td = upload_full(w)
-    tv = torch.empty_like(tu)
-    for name in variants_for(w.n, w.dtype):
+    outs = {}
+    for name in variants_for(w.n, w.dtype) + ["auto"]:
         print(f"case {w.name} variant={name}", flush=True)
-        tv.fill_(float("nan"))
-        tpo.apply_tensors(tu, tsx, tsy, tsz, td, tv, variant=VARIANTS[name])
+        tv = torch.full_like(tu, float("nan"))
+        if name == "auto":          # the 10-argument entry point, the call the benchmark times
+            rc = tpo.tpo_ihelm_apply(tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(),
+                                     td.data_ptr(), tv.data_ptr(), w.n, w.num_elems, DT[w.dtype],
+                                     torch.cuda.current_stream().cuda_stream)
+            assert rc == tpo.TPO_OK
+        else:
+            tpo.apply_tensors(tu, tsx, tsy, tsz, td, tv, variant=VARIANTS[name])
         torch.cuda.synchronize()
-        # (1) oracle on sampled windows, element by element
-        sx, sy, sz = wl.direction_matrices(w)
-        worst = 0.0
-        for lo, hi in sample_spans(w.num_elems):
-            u = wl.field_u(w, lo, hi)
-            d = wl.diagonal_d(w, lo, hi)
-            assert np.array_equal(u, tu[lo:hi].cpu().numpy())      # same inputs on both sides
-            ref = oracle.ihelm_apply(u, sx, sy, sz, d)
-            err = oracle.max_rel_err_per_element(tv[lo:hi].cpu().numpy(), ref)
-            worst = max(worst, err)
-        assert worst <= TOL[w.dtype], f"{w.name} {name}: sampled err {worst:.3e}"
-        # (2) every element: no NaN left, and agreement with a device einsum in fp64
         assert not torch.isnan(tv).any()
-        step = 8192
-        worst_all = 0.0
-        s64 = [s.double() for s in (tsx, tsy, tsz)]
-        for lo in range(0, w.num_elems, step):
-            hi = min(w.num_elems, lo + step)
-            ref = torch_reference_chunk(tu[lo:hi].double(), *s64, td[lo:hi].double())
-            num = (tv[lo:hi].double() - ref).abs().flatten(1).max(dim=1).values
-            den = ref.abs().flatten(1).max(dim=1).values
-            worst_all = max(worst_all, float((num / den).max()))
-        assert worst_all <= TOL[w.dtype], f"{w.name} {name}: full err {worst_all:.3e}"
-        print(f"  {w.name} {name}: sampled {worst:.2e}, all elements {worst_all:.2e}", flush=True)
+        outs[name] = tv
+    print(f"case {w.name}: oracle over all {w.num_elems} elements", flush=True)
+    worst = oracle_over_all_elements(w, tu, td, outs)
+    print(f"  {w.name}: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()), flush=True)
+
+
+# the paper's batch (Sec. 6.1: 8192 elements per call) with the shapes of the four large
+# configurations: the 10-argument entry point and the separable form, every element against the
+# oracle
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_paper_batch_8192(idx):
+    c = wl.CONFIGS[idx]
+    w = wl.Workload(c.name + "_E8192", c.index, c.dtype, c.n, 8192, c.u_dist, c.distinct_s)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    tu, td = dev(u), dev(d)
+    if sx is sy and sy is sz:
+        tsx = tsy = tsz = dev(sx)
+    else:
+        tsx, tsy, tsz = dev(sx), dev(sy), dev(sz)
+    tv = torch.full_like(tu, float("nan"))
+    rc = tpo.tpo_ihelm_apply(tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(),
+                             td.data_ptr(), tv.data_ptr(), w.n, w.num_elems, DT[w.dtype],
+                             torch.cuda.current_stream().cuda_stream)
+    assert rc == tpo.TPO_OK
+    torch.cuda.synchronize()
+    err = oracle.max_rel_err_per_element(tv.cpu().numpy(), ref)
+    assert err <= TOL[w.dtype], f"{w.name}: err {err:.3e}"
+    lam = wl.sep_inputs(w)
+    ref_sep = oracle.ihelm_apply_sep(u, sx, sy, sz, *lam)
+    tv.fill_(float("nan"))
+    tpo.apply_sep_tensors(tu, tsx, tsy, tsz, *map(dev, lam), v=tv)
+    torch.cuda.synchronize()
+    err_sep = oracle.max_rel_err_per_element(tv.cpu().numpy(), ref_sep)
+    assert err_sep <= TOL[w.dtype], f"{w.name} sep: err {err_sep:.3e}"
+    print(f"  {w.name}: {err:.2e}, separable {err_sep:.2e}", flush=True)
+
+
+# fp32 n = 14, 15, 16: the family the 10-argument entry point takes there (matrix-core tiles)
+# at the batch size of the large workloads, every element against the oracle
+@pytest.mark.parametrize("n", [14, 15, 16])
+def test_f32_large_n_at_scale(n):
+    w = wl.custom(n, 262144 + 37, "f32", key=900 + n, distinct_s=True)
+    assert tpo.tpo_ihelm_variant_for(n, tpo.TPO_F32, 0) == tpo.TPO_VARIANT_MFMA
+    print(f"case f32 n={n} E={w.num_elems}: generating", flush=True)
+    tu, tsx, tsy, tsz, td = upload_full(w)
+    tv = torch.full_like(tu, float("nan"))
+    rc = tpo.tpo_ihelm_apply(tu.data_ptr(), tsx.data_ptr(), tsy.data_ptr(), tsz.data_ptr(),
+                             td.data_ptr(), tv.data_ptr(), n, w.num_elems, tpo.TPO_F32,
+                             torch.cuda.current_stream().cuda_stream)
+    assert rc == tpo.TPO_OK
+    torch.cuda.synchronize()
+    assert not torch.isnan(tv).any()
+    worst = oracle_over_all_elements(w, tu, td, {"auto": tv})
+    print(f"  f32 n={n}: {worst['auto']:.2e}", flush=True)
+
+
+# the persistent matrix-core kernel (fp64 n = 11: a fixed grid of workgroups walks over the
+# elements): batches larger than the resident grid so that every workgroup iterates, with a
+# ragged tail, out of place and in place
+@pytest.mark.parametrize("e", [4099, 20011])
+def test_persistent_mfma_loop_iterates(e):
+    w = wl.custom(11, e, "f64", key=1400 + e % 7, distinct_s=True)
+    u, sx, sy, sz, d = wl.make_inputs(w)
+    ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+    tu, tsx, tsy, tsz, td = map(dev, (u, sx, sy, sz, d))
+    var = tpo.TPO_VARIANT_MFMA
+    v1 = tpo.apply_tensors(tu, tsx, tsy, tsz, td, variant=var)
+    torch.cuda.synchronize()
+    assert oracle.max_rel_err_per_element(v1.cpu().numpy(), ref) <= TOL["f64"]
+    v2 = tpo.apply_tensors(tu, tsx, tsy, tsz, td, variant=var)
+    assert torch.equal(v1, v2)
+    tpo.apply_tensors(tu, tsx, tsy, tsz, td, tu, variant=var)        # v == u
+    torch.cuda.synchronize()
+    assert torch.equal(tu, v1)
+    # one matrix shared by the three directions: the other instantiation of the same loop
+    w2 = wl.custom(11, e, "f64", key=1410 + e % 7, distinct_s=False)
+    u, sx, sy, sz, d = wl.make_inputs(w2)
+    got = run(u, sx, sy, sz, d, var)
+    assert oracle.max_rel_err_per_element(got, oracle.ihelm_apply(u, sx, sy, sz, d)) <= TOL["f64"]
 
 
 # small n with millions of elements: many workgroups per launch, several elements per
