@@ -113,7 +113,8 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
                             const void *D, void *v, int n, long long num_elems, int dtype,
                             void *stream, int variant);
 
-/* tpo_ihelm_variant_for -- which family TPO_VARIANT_AUTO selects for (n, dtype).
+/* tpo_ihelm_variant_for -- which family TPO_VARIANT_AUTO selects for (n, dtype) on a large
+ * batch (the choice can depend on the batch size: see tpo_ihelm_variant_for_batch).
  * shared_s != 0 asks about calls that pass ONE matrix for all three directions (S_x, S_y and
  * S_z are the same pointer), 0 about calls with distinct pointers; the choice can differ
  * because the matrix-core kernels hold a shared matrix once.
@@ -121,6 +122,13 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
  * TPO_ERR_INVALID_ARG.
  * Pure host function; needs no device. */
 int tpo_ihelm_variant_for(int n, int dtype, int shared_s);
+
+/* tpo_ihelm_variant_for_batch -- the family TPO_VARIANT_AUTO selects for a call with
+ * num_elems elements (the paper times 8192 elements per call, Sec. 6.1; with a few thousand
+ * workgroups per launch another family can be ahead of the large-batch choice).  Arguments,
+ * return values and errors as tpo_ihelm_variant_for; num_elems < 0 is TPO_ERR_INVALID_ARG.
+ * Pure host function; needs no device. */
+int tpo_ihelm_variant_for_batch(int n, int dtype, int shared_s, long long num_elems);
 
 /* tpo_ihelm_has_variant -- 1 if `variant` has a kernel for (n, dtype), else 0
  * (TPO_VARIANT_AUTO always has one for supported n). */

@@ -15,13 +15,18 @@ std::mutex g_mu;
 int g_refs[kMaxDevices] = {0};
 
 // Family chosen by TPO_VARIANT_AUTO, from measurements on MI355X.
-int auto_variant(int n, int dtype, bool shared_s)
+int auto_variant(int n, int dtype, bool shared_s, long long num_elems)
 {
     // Measured on MI355X at the sizes of the named workloads (ms per launch, pencil / MFMA):
     // fp64 n=8 0.25 / 0.27, n=11 1.46 / 1.69, fp32 n=13 5.99 / 6.09: pencil.
     // fp64 n=16: pencil 1.19; MFMA 1.16 when one matrix is shared by the three directions
     // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
-    if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
+    // Between about 3000 and 12000 elements the pencil kernel is ahead there (E = 4096: 75.6
+    // against 79.3 us, 8192: 139 against 145; E = 2048: 46.6 against 38.3, from 16384 on the
+    // matrix-core kernel leads again): the launch is a few rounds of resident workgroups, and
+    // the pencil kernel's rounds (4 workgroups per CU against 3) divide such batches better.
+    if (dtype == TPO_F64 && n == 16 && shared_s)
+        return (num_elems > 3072 && num_elems <= 12288) ? TPO_VARIANT_PENCIL : TPO_VARIANT_MFMA;
     // fp32: with 4x4x1 matrix-core products the pencil kernel leaves the vector-FMA bound
     // (n=13, E=1048576: 5.5 against 6.0 ms).  All three families on 1 GiB fields, every n, each at
     // its best setting (GB/s, vector-FMA pencil / 4x4x1 pencil / MFMA tiles): n=8 6079/5853/4790,
@@ -131,14 +136,19 @@ int tpo_destroy(void)
     return TPO_OK;
 }
 
-int tpo_ihelm_variant_for(int n, int dtype, int shared_s)
+int tpo_ihelm_variant_for_batch(int n, int dtype, int shared_s, long long num_elems)
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
-    if (n < 1) return TPO_ERR_INVALID_ARG;
+    if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
-    int var = auto_variant(n, dtype, shared_s != 0);
+    int var = auto_variant(n, dtype, shared_s != 0, num_elems);
     if (!lookup(n, dtype, var)) var = TPO_VARIANT_PENCIL;
     return var;
+}
+
+int tpo_ihelm_variant_for(int n, int dtype, int shared_s)
+{
+    return tpo_ihelm_variant_for_batch(n, dtype, shared_s, 1LL << 40);
 }
 
 int tpo_ihelm_has_variant(int n, int dtype, int variant)
@@ -156,7 +166,7 @@ int tpo_ihelm_apply_variant(const void *u, const void *S_x, const void *S_y, con
     const int rc = tpo::validate_apply(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, variant);
     if (rc != TPO_OK) return rc;
     if (variant == TPO_VARIANT_AUTO)
-        variant = tpo_ihelm_variant_for(n, dtype, S_x == S_y && S_y == S_z);
+        variant = tpo_ihelm_variant_for_batch(n, dtype, S_x == S_y && S_y == S_z, num_elems);
     const tpo::KernelEntry *k = lookup(n, dtype, variant);
     if (!k) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;
@@ -210,7 +220,7 @@ int tpo_ihelm_sep_variant_for(int n, int dtype)
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
     // The matrix-core tile kernels have no separable-diagonal form; where the D form takes them,
     // this form takes the best pencil family instead (fp32 n >= 8: the 4x4x1 kernels).
-    int var = auto_variant(n, dtype, false);
+    int var = auto_variant(n, dtype, false, 1LL << 40);
     const tpo::KernelEntry *k = lookup(n, dtype, var);
     if (!k || !k->launch_sep)
         var = (dtype == TPO_F32 && n >= 8) ? TPO_VARIANT_PENCIL_MM : TPO_VARIANT_PENCIL;

@@ -357,6 +357,32 @@ template <> struct PencilTune<double, 11> {
     static constexpr size_t LDS_MIN = 18 * 1024;
 };
 
+// Settings for small batches, used when LO < num_elems <= HI (HI = 0: never).  With a few
+// thousand workgroups the launch is a handful of rounds of resident workgroups: how the rounds
+// divide the batch and how fast a round drains count for more than the steady-state memory
+// behaviour the large-batch settings were chosen for.  From sweeps over E = 2048 .. 131072 on
+// MI355X (the batch of 8192 elements per call is the one the paper times, Sec. 6.1):
+//  * n = 11: up to 65536 elements the die renumbering and the occupancy cap cost more than they
+//    save (E = 4096: 25.3 against 27.8 us, 16384: 97.6 against 101.2, 32768: 189 against 196,
+//    65536: 374 against 377; from 98304 on the large-batch settings are ahead again);
+//  * n = 8: between 4096 and 24576 elements one element per workgroup with cached accesses and
+//    D_e in its pencil layout beats four per workgroup (8192: 19.5 against 20.5 us, 16384: 33.2
+//    against 35.9); at 4096 and from 32768 on the large-batch settings win.
+template <typename T, int N>
+struct PencilSmallTune : PencilTune<T, N> {
+    static constexpr long long LO = 0, HI = 0;
+};
+template <> struct PencilSmallTune<double, 11> : PencilTune<double, 11> {
+    static constexpr bool XCD = false;
+    static constexpr size_t LDS_MIN = 0;
+    static constexpr long long LO = 0, HI = 65536;
+};
+template <> struct PencilSmallTune<double, 8> : PencilTune<double, 8> {
+    static constexpr int G = 1, HINT = 0;
+    static constexpr bool DDIRECT = true;
+    static constexpr long long LO = 4096, HI = 24576;
+};
+
 // Tuning of the separable-diagonal form: as the D form unless measured otherwise.  Without the
 // D_e stream a workgroup has half the loads in flight, so the D form's occupancy cap at n = 11
 // and its four elements per workgroup at n = 8 no longer pay (n = 11: 1.27 against 1.35 ms;
@@ -407,12 +433,19 @@ struct PencilLauncherT {
 template <typename T, int N>
 struct PencilLauncher {
     using Plain = PencilLauncherT<T, N, PencilTune<T, N>, 0>;
+    using Small = PencilLauncherT<T, N, PencilSmallTune<T, N>, 0>;
     using Sep = PencilLauncherT<T, N, PencilSepTune<T, N>, 2>;   // fast reciprocal
-    static hipError_t launch(const ApplyArgs &a) { return Plain::launch(a); }
+    static hipError_t launch(const ApplyArgs &a)
+    {
+        using St = PencilSmallTune<T, N>;
+        if (a.num_elems > St::LO && a.num_elems <= St::HI) return Small::launch(a);
+        return Plain::launch(a);
+    }
     static hipError_t launch_sep(const ApplyArgs &a) { return Sep::launch(a); }
     static hipError_t prepare()
     {
-        const hipError_t rc = Plain::prepare();
+        hipError_t rc = Plain::prepare();
+        if (rc == hipSuccess) rc = Small::prepare();
         return rc != hipSuccess ? rc : Sep::prepare();
     }
 };

@@ -47,6 +47,8 @@ def lib():
         l.tpo_ihelm_apply_variant.restype = ci
         l.tpo_ihelm_variant_for.argtypes = [ci, ci, ci]
         l.tpo_ihelm_variant_for.restype = ci
+        l.tpo_ihelm_variant_for_batch.argtypes = [ci, ci, ci, ctypes.c_longlong]
+        l.tpo_ihelm_variant_for_batch.restype = ci
         l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_has_variant.restype = ci
         l.tpo_ihelm_apply_sep.argtypes = [vp] * 9 + [ci, cll, ci, vp]
@@ -99,6 +101,11 @@ def tpo_ihelm_apply_variant(u, S_x, S_y, S_z, D, v, n, num_elems, dtype, stream,
 
 def tpo_ihelm_variant_for(n: int, dtype: int, shared_s: bool = False) -> int:
     return lib().tpo_ihelm_variant_for(int(n), int(dtype), int(bool(shared_s)))
+
+
+def tpo_ihelm_variant_for_batch(n: int, dtype: int, shared_s: bool, num_elems: int) -> int:
+    return lib().tpo_ihelm_variant_for_batch(int(n), int(dtype), int(bool(shared_s)),
+                                             int(num_elems))
 
 
 def tpo_ihelm_has_variant(n: int, dtype: int, variant: int) -> bool:

@@ -47,6 +47,8 @@ int main(void)
     }
     bad += tpo_convection_has_shape(8, 12, TPO_F64) != 1;
     bad += tpo_ihelm_variant_for(11, TPO_F64, 1) != TPO_VARIANT_PENCIL;
+    bad += tpo_ihelm_variant_for_batch(16, TPO_F64, 1, 1 << 20) != TPO_VARIANT_MFMA;
+    bad += tpo_ihelm_variant_for_batch(16, TPO_F64, 1, -1) != TPO_ERR_INVALID_ARG;
     printf("abi_check: %d unexpected status(es)\n", bad);
     return bad;
 }

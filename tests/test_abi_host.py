@@ -227,4 +227,15 @@ def test_variant_queries():
     assert tpo.tpo_ihelm_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
     assert tpo.tpo_ihelm_variant_for(0, tpo.TPO_F64) == tpo.TPO_ERR_INVALID_ARG
     assert tpo.tpo_ihelm_variant_for(4, 5) == tpo.TPO_ERR_INVALID_ARG
+    # the batch-aware query: equal to the plain one for large batches; fp64 n=16 with a shared
+    # matrix takes the pencil kernels around the paper's batch of 8192 elements
+    for dt in (tpo.TPO_F64, tpo.TPO_F32):
+        for n in range(1, 17):
+            for shared in (False, True):
+                assert tpo.tpo_ihelm_variant_for_batch(n, dt, shared, 1 << 22) \
+                    == tpo.tpo_ihelm_variant_for(n, dt, shared)
+    assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, True, 8192) == tpo.TPO_VARIANT_PENCIL
+    assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, True, 65536) == tpo.TPO_VARIANT_MFMA
+    assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, False, 8192) == tpo.TPO_VARIANT_PENCIL
+    assert tpo.tpo_ihelm_variant_for_batch(4, tpo.TPO_F64, True, -1) == tpo.TPO_ERR_INVALID_ARG
     assert not tpo.tpo_ihelm_has_variant(17, tpo.TPO_F64, tpo.TPO_VARIANT_PENCIL)
