@@ -316,6 +316,7 @@ def main() -> int:
                          "convection volume term; aniso: the operator on anisotropic elements "
                          "(--workload indexes the configurations of these two on their own)")
     ap.add_argument("--elems", type=int, default=0, help="override the element count (experiments)")
+    ap.add_argument("--n", type=int, default=0, help="override the points per direction (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=262144,
                     help="elements the CPU oracle is timed on (all host threads)")
@@ -348,6 +349,9 @@ def main() -> int:
     if args.elems:
         w = wl.Workload(w.name + f"_E{args.elems}", w.index, w.dtype, w.n, args.elems,
                         w.u_dist, w.distinct_s)
+    if args.n:
+        w = wl.Workload(w.name + f"_n{args.n}", w.index, w.dtype, args.n, w.num_elems,
+                        w.u_dist, w.distinct_s)
     variant = {"auto": tpo.TPO_VARIANT_AUTO, "pencil": tpo.TPO_VARIANT_PENCIL,
                "mfma": tpo.TPO_VARIANT_MFMA,
                "pencil_mm": tpo.TPO_VARIANT_PENCIL_MM}[args.variant]
@@ -360,7 +364,7 @@ def main() -> int:
             return 2
         chosen = tpo.TPO_VARIANT_PENCIL
     elif sep:
-        chosen = variant or tpo.tpo_ihelm_sep_variant_for(w.n, dt)
+        chosen = variant or tpo.tpo_ihelm_sep_variant_for_batch(w.n, dt, not w.distinct_s, w.num_elems)
     else:
         chosen = variant or tpo.tpo_ihelm_variant_for_batch(w.n, dt, not w.distinct_s, w.num_elems)
     chosen_name = {tpo.TPO_VARIANT_PENCIL: "pencil", tpo.TPO_VARIANT_MFMA: "mfma",

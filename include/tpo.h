@@ -157,20 +157,22 @@ int tpo_ihelm_has_variant(int n, int dtype, int variant);
  * agrees with tpo_ihelm_apply on an IEEE-divided D_e to a few ulp, not bit for bit.  A zero
  * denominator gives Inf/NaN; it is not checked.
  * Errors: as tpo_ihelm_apply (v must not overlap lam_* or mu either); TPO_ERR_UNSUPPORTED
- * from the _variant form when the family has no separable form for (n, dtype) (the matrix-core
- * tile kernels have none).
+ * from the _variant form when the family has no kernel for (n, dtype).
  */
 int tpo_ihelm_apply_sep(const void *u, const void *S_x, const void *S_y, const void *S_z,
                         const void *lam_x, const void *lam_y, const void *lam_z, const void *mu,
                         void *v, int n, long long num_elems, int dtype, void *stream);
 
-/* The same with the kernel family forced, and the two queries that go with it (which family
- * TPO_VARIANT_AUTO selects; whether a family has a separable form for (n, dtype)). */
+/* The same with the kernel family forced, and the queries that go with it: which family
+ * TPO_VARIANT_AUTO selects (tpo_ihelm_sep_variant_for: three distinct matrix pointers, large
+ * batch; tpo_ihelm_sep_variant_for_batch: for shared_s and num_elems as in
+ * tpo_ihelm_variant_for_batch), and whether a family has a separable form for (n, dtype). */
 int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y, const void *S_z,
                                 const void *lam_x, const void *lam_y, const void *lam_z,
                                 const void *mu, void *v, int n, long long num_elems, int dtype,
                                 void *stream, int variant);
 int tpo_ihelm_sep_variant_for(int n, int dtype);
+int tpo_ihelm_sep_variant_for_batch(int n, int dtype, int shared_s, long long num_elems);
 int tpo_ihelm_sep_has_variant(int n, int dtype, int variant);
 
 /*

@@ -213,18 +213,25 @@ int tpo_transform_apply(const void *u, const void *S_x, const void *S_y, const v
     return launch_status(direction == TPO_FORWARD ? k->launch_forward(a) : k->launch_backward(a));
 }
 
-int tpo_ihelm_sep_variant_for(int n, int dtype)
+int tpo_ihelm_sep_variant_for_batch(int n, int dtype, int shared_s, long long num_elems)
 {
     if (dtype != TPO_F64 && dtype != TPO_F32) return TPO_ERR_INVALID_ARG;
-    if (n < 1) return TPO_ERR_INVALID_ARG;
+    if (n < 1 || num_elems < 0) return TPO_ERR_INVALID_ARG;
     if (n > TPO_MAX_N) return TPO_ERR_UNSUPPORTED;
-    // The matrix-core tile kernels have no separable-diagonal form; where the D form takes them,
-    // this form takes the best pencil family instead (fp32 n >= 8: the 4x4x1 kernels).
-    int var = auto_variant(n, dtype, false, 1LL << 40);
+    // Every family has the separable form, and the D form's choice holds for it too.  Measured
+    // on MI355X (ms per launch, best pencil family / matrix-core tiles): fp64 n=16, E=65536, one
+    // shared matrix 1.112 / 1.052; fp32, E=262144: n=14 2.038 / 2.029, n=15 2.323 / 2.203,
+    // n=16 2.407 / 2.070.
+    int var = auto_variant(n, dtype, shared_s != 0, num_elems);
     const tpo::KernelEntry *k = lookup(n, dtype, var);
     if (!k || !k->launch_sep)
         var = (dtype == TPO_F32 && n >= 8) ? TPO_VARIANT_PENCIL_MM : TPO_VARIANT_PENCIL;
     return var;
+}
+
+int tpo_ihelm_sep_variant_for(int n, int dtype)
+{
+    return tpo_ihelm_sep_variant_for_batch(n, dtype, 0, 1LL << 40);
 }
 
 int tpo_ihelm_sep_has_variant(int n, int dtype, int variant)
@@ -244,7 +251,8 @@ int tpo_ihelm_apply_sep_variant(const void *u, const void *S_x, const void *S_y,
     const int rc = tpo::validate_apply_sep(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n,
                                            num_elems, dtype, variant);
     if (rc != TPO_OK) return rc;
-    if (variant == TPO_VARIANT_AUTO) variant = tpo_ihelm_sep_variant_for(n, dtype);
+    if (variant == TPO_VARIANT_AUTO)
+        variant = tpo_ihelm_sep_variant_for_batch(n, dtype, S_x == S_y && S_y == S_z, num_elems);
     const tpo::KernelEntry *k = lookup(n, dtype, variant);
     if (!k || !k->launch_sep) return TPO_ERR_UNSUPPORTED;
     if (num_elems == 0) return TPO_OK;

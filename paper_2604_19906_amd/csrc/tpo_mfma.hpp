@@ -81,13 +81,18 @@ struct MfmaShape {
 // SAMES = true: the caller passed one matrix for all three directions (equal pointers); the A
 // operands are then held once instead of three times (for n = 16 in fp64 that is 32 VGPRs,
 // the difference between three and four wavefronts per SIMD).
+// SEP != 0: D is not read; every lane evaluates the D_e entries of its accumulator layout from
+// the separable form 1 / (((lam_x[a] + lam_y[b]) + lam_z[c]) + mu[e]) (SEP = 1: IEEE division,
+// 2: recip_<false>) where the D form loads them; D is ignored and may be null.
 template <typename T, int N, int G, int NW, int HINT, bool PERSIST, bool SAMES, int WAVES,
-          bool XCD = false>
+          bool XCD = false, int SEP = 0>
 __global__ void __launch_bounds__((MfmaShape<T, N, G, NW>::NT))
 __attribute__((amdgpu_waves_per_eu(WAVES)))
 ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy,
                   const T *__restrict__ Sz, const T *__restrict__ D, T *v,
-                  long long num_elems)
+                  long long num_elems, const T *__restrict__ lam_x = nullptr,
+                  const T *__restrict__ lam_y = nullptr, const T *__restrict__ lam_z = nullptr,
+                  const T *__restrict__ mu = nullptr)
 {
     using Sh = MfmaShape<T, N, G, NW>;
     using M = Mfma<T>;
@@ -144,6 +149,8 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     int o2z[TPW], o0z[TPW];            // the same for element 0 of the batch
     int gel[TPW];                      // element slot of the tile (uniform over the wavefront)
     bool colst[TPW];                   // the lane's column exists in a full batch
+    T lam_bc[SEP != 0 ? TPW : 1][2];   // lam_y[b], lam_z[c] of the lane's column (b, c), per tile
+    T lam_a[SEP != 0 ? KS : 1];        // lam_x[off + r]: the axis-0 indices of the lane's rows
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
         const int tt = wave + NW * j;
@@ -161,6 +168,14 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
         o0z[j] = X + off * P2;
         o2[j] = ge * N3 + o2z[j];
         o0[j] = ge * N3 + o0z[j];
+        if constexpr (SEP != 0) {
+            lam_bc[j][0] = lam_y[hi];
+            lam_bc[j][1] = lam_z[lo];
+        }
+    }
+    if constexpr (SEP != 0) {
+#pragma unroll
+        for (int r = 0; r < KS; ++r) lam_a[r] = lam_x[off + r];
     }
 
     T un[TPW][KS];      // u_e chunks of the batch about to be computed (B operands, axis 2)
@@ -176,12 +191,22 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
     };
     auto load_d = [&](long long batch) {
         const long long left = num_elems - batch * G;
-        const T *db = D + (size_t)batch * (size_t)(G * N3);
+        if constexpr (SEP != 0) {
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-            const T *dp = db + (gel[j] < left ? o0[j] : o0z[j]);
+            for (int j = 0; j < TPW; ++j) {
+                const T mu_e = mu[batch * G + (gel[j] < left ? gel[j] : 0)];
 #pragma unroll
-            for (int r = 0; r < KS; ++r) dreg[j][r] = gload<LD_NT>(dp + r * P2);
+                for (int r = 0; r < KS; ++r)
+                    dreg[j][r] = recip_<SEP == 1>(((lam_a[r] + lam_bc[j][0]) + lam_bc[j][1]) + mu_e);
+            }
+        } else {
+            const T *db = D + (size_t)batch * (size_t)(G * N3);
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                const T *dp = db + (gel[j] < left ? o0[j] : o0z[j]);
+#pragma unroll
+                for (int r = 0; r < KS; ++r) dreg[j][r] = gload<LD_NT>(dp + r * P2);
+            }
         }
     };
 
@@ -304,23 +329,25 @@ ihelm_mfma_kernel(const T *u, const T *__restrict__ Sx, const T *__restrict__ Sy
 template <typename T, int N, int G, int NW, int HINT, bool PERSIST, int WAVES, bool XCD = false>
 struct MfmaLauncher {
     using Sh = MfmaShape<T, N, G, NW>;
-    static inline int wgs_per_device[2] = {0, 0};       // [SAMES]
+    static inline int wgs_per_device[4] = {0, 0, 0, 0};       // [SAMES + 2 * (SEP != 0)]
 
-    template <bool SAMES>
+    template <bool SAMES, int SEP = 0>
     static hipError_t launch_as(const ApplyArgs &a)
     {
         const long long nbatch = (a.num_elems + G - 1) / G;
         if (nbatch <= 0 || nbatch > 0x7fffffffLL) return kGridTooLarge;
         long long blocks = PERSIST ? nbatch : pencil_grid<XCD>(nbatch);
         if (PERSIST) {
-            if (wgs_per_device[SAMES] <= 0) return hipErrorNotInitialized;
-            if (blocks > wgs_per_device[SAMES]) blocks = wgs_per_device[SAMES];
+            constexpr int slot = SAMES + 2 * (SEP != 0);
+            if (wgs_per_device[slot] <= 0) return hipErrorNotInitialized;
+            if (blocks > wgs_per_device[slot]) blocks = wgs_per_device[slot];
         }
         drop_stale_error();
-        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD>),
+        hipLaunchKernelGGL((ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD, SEP>),
                            dim3((unsigned)blocks), dim3(Sh::NT), Sh::LDS_BYTES, a.stream,
                            (const T *)a.u, (const T *)a.sx, (const T *)a.sy, (const T *)a.sz,
-                           (const T *)a.d, (T *)a.v, a.num_elems);
+                           (const T *)a.d, (T *)a.v, a.num_elems, (const T *)a.lam_x,
+                           (const T *)a.lam_y, (const T *)a.lam_z, (const T *)a.mu);
         return hipGetLastError();
     }
 
@@ -328,11 +355,16 @@ struct MfmaLauncher {
     {
         return (a.sx == a.sy && a.sy == a.sz) ? launch_as<true>(a) : launch_as<false>(a);
     }
+    // separable diagonal, hardware reciprocal (as the pencil families)
+    static hipError_t launch_sep(const ApplyArgs &a)
+    {
+        return (a.sx == a.sy && a.sy == a.sz) ? launch_as<true, 2>(a) : launch_as<false, 2>(a);
+    }
 
-    template <bool SAMES>
+    template <bool SAMES, int SEP = 0>
     static hipError_t prepare_as()
     {
-        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD>;
+        const void *fn = (const void *)ihelm_mfma_kernel<T, N, G, NW, HINT, PERSIST, SAMES, WAVES, XCD, SEP>;
         if (Sh::LDS_BYTES > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)Sh::LDS_BYTES);
@@ -347,7 +379,7 @@ struct MfmaLauncher {
             e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, Sh::NT, Sh::LDS_BYTES);
             if (e != hipSuccess) return e;
             if (per_cu < 1) per_cu = 1;
-            wgs_per_device[SAMES] = cus * per_cu;
+            wgs_per_device[SAMES + 2 * (SEP != 0)] = cus * per_cu;
         }
         return hipSuccess;
     }
@@ -355,7 +387,9 @@ struct MfmaLauncher {
     static hipError_t prepare()
     {
         hipError_t e = prepare_as<false>();
-        return e != hipSuccess ? e : prepare_as<true>();
+        if (e == hipSuccess) e = prepare_as<true>();
+        if (e == hipSuccess) e = prepare_as<false, 2>();
+        return e != hipSuccess ? e : prepare_as<true, 2>();
     }
 };
 

@@ -16,14 +16,10 @@ struct MfmaTune_f32 {
     static constexpr bool XCD = false;
 };
 
-#define ENTRY(N)                                                                          \
-    KernelEntry {                                                                         \
-        &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES, MfmaTune_f32<N>::XCD>::launch,                                   \
-        nullptr,                                                                          \
-        &MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW,               \
-                      MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST, MfmaTune_f32<N>::WAVES, MfmaTune_f32<N>::XCD>::prepare                                   \
-    }
+template <int N>
+using Launcher = MfmaLauncher<float, N, MfmaTune_f32<N>::G, MfmaTune_f32<N>::NW, MfmaTune_f32<N>::HINT, MfmaTune_f32<N>::PERSIST,
+                              MfmaTune_f32<N>::WAVES, MfmaTune_f32<N>::XCD>;
+#define ENTRY(N) KernelEntry { &Launcher<N>::launch, &Launcher<N>::launch_sep, &Launcher<N>::prepare }
 
 const KernelEntry *mfma_entry_f32(int n)
 {

@@ -38,14 +38,10 @@ struct MfmaTune_f64<11> {
     static constexpr bool XCD = false;
 };
 
-#define ENTRY(N)                                                                          \
-    KernelEntry {                                                                         \
-        &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES, MfmaTune_f64<N>::XCD>::launch,                                   \
-        nullptr,                                                                          \
-        &MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW,               \
-                      MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST, MfmaTune_f64<N>::WAVES, MfmaTune_f64<N>::XCD>::prepare                                   \
-    }
+template <int N>
+using Launcher = MfmaLauncher<double, N, MfmaTune_f64<N>::G, MfmaTune_f64<N>::NW, MfmaTune_f64<N>::HINT, MfmaTune_f64<N>::PERSIST,
+                              MfmaTune_f64<N>::WAVES, MfmaTune_f64<N>::XCD>;
+#define ENTRY(N) KernelEntry { &Launcher<N>::launch, &Launcher<N>::launch_sep, &Launcher<N>::prepare }
 
 const KernelEntry *mfma_entry_f64(int n)
 {

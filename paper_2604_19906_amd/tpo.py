@@ -47,7 +47,7 @@ def lib():
         l.tpo_ihelm_apply_variant.restype = ci
         l.tpo_ihelm_variant_for.argtypes = [ci, ci, ci]
         l.tpo_ihelm_variant_for.restype = ci
-        l.tpo_ihelm_variant_for_batch.argtypes = [ci, ci, ci, ctypes.c_longlong]
+        l.tpo_ihelm_variant_for_batch.argtypes = [ci, ci, ci, cll]
         l.tpo_ihelm_variant_for_batch.restype = ci
         l.tpo_ihelm_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_has_variant.restype = ci
@@ -57,6 +57,8 @@ def lib():
         l.tpo_ihelm_apply_sep_variant.restype = ci
         l.tpo_ihelm_sep_variant_for.argtypes = [ci, ci]
         l.tpo_ihelm_sep_variant_for.restype = ci
+        l.tpo_ihelm_sep_variant_for_batch.argtypes = [ci, ci, ci, cll]
+        l.tpo_ihelm_sep_variant_for_batch.restype = ci
         l.tpo_ihelm_sep_has_variant.argtypes = [ci, ci, ci]
         l.tpo_ihelm_sep_has_variant.restype = ci
         l.tpo_ihelm_apply_aniso.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, cll, ci, vp]
@@ -128,6 +130,11 @@ def tpo_ihelm_apply_sep_variant(u, S_x, S_y, S_z, lam_x, lam_y, lam_z, mu, v, n,
 
 def tpo_ihelm_sep_variant_for(n: int, dtype: int) -> int:
     return lib().tpo_ihelm_sep_variant_for(int(n), int(dtype))
+
+
+def tpo_ihelm_sep_variant_for_batch(n: int, dtype: int, shared_s: bool, num_elems: int) -> int:
+    return lib().tpo_ihelm_sep_variant_for_batch(int(n), int(dtype), int(bool(shared_s)),
+                                                 int(num_elems))
 
 
 def tpo_ihelm_sep_has_variant(n: int, dtype: int, variant: int) -> bool:

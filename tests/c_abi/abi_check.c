@@ -49,6 +49,7 @@ int main(void)
     bad += tpo_ihelm_variant_for(11, TPO_F64, 1) != TPO_VARIANT_PENCIL;
     bad += tpo_ihelm_variant_for_batch(16, TPO_F64, 1, 1 << 20) != TPO_VARIANT_MFMA;
     bad += tpo_ihelm_variant_for_batch(16, TPO_F64, 1, -1) != TPO_ERR_INVALID_ARG;
+    bad += tpo_ihelm_sep_variant_for_batch(16, TPO_F64, 1, 1 << 20) != TPO_VARIANT_MFMA;
     printf("abi_check: %d unexpected status(es)\n", bad);
     return bad;
 }

@@ -118,7 +118,7 @@ def test_sep_argument_validation():
     assert tpo.tpo_ihelm_apply_sep_variant(u, sx, sy, sz, lx, ly, lz, mu, v, n, e, tpo.TPO_F64,
                                            None, 9) == tpo.TPO_ERR_INVALID_ARG
     assert tpo.tpo_ihelm_apply_sep_variant(u, sx, sy, sz, lx, ly, lz, mu, v, n, e, tpo.TPO_F64,
-                                           None, tpo.TPO_VARIANT_MFMA) == tpo.TPO_ERR_UNSUPPORTED
+                                           None, tpo.TPO_VARIANT_PENCIL_MM) == tpo.TPO_ERR_UNSUPPORTED
 
 
 def test_transform_argument_validation():
@@ -206,8 +206,18 @@ def test_sep_variant_queries():
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, var)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_AUTO)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
-            assert not tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_MFMA)
+            assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_MFMA)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL_MM) == (dt == tpo.TPO_F32)
+    # the separable form follows the D form's choice of family, batch-aware query included
+    assert tpo.tpo_ihelm_sep_variant_for_batch(16, tpo.TPO_F64, True, 65536) == tpo.TPO_VARIANT_MFMA
+    assert tpo.tpo_ihelm_sep_variant_for_batch(16, tpo.TPO_F64, False, 65536) == tpo.TPO_VARIANT_PENCIL
+    assert tpo.tpo_ihelm_sep_variant_for_batch(15, tpo.TPO_F32, False, 65536) == tpo.TPO_VARIANT_MFMA
+    assert tpo.tpo_ihelm_sep_variant_for_batch(13, tpo.TPO_F32, False, 65536) == tpo.TPO_VARIANT_PENCIL_MM
+    assert tpo.tpo_ihelm_sep_variant_for_batch(13, tpo.TPO_F32, False, -2) == tpo.TPO_ERR_INVALID_ARG
+    for n in range(1, 17):
+        for dt in (tpo.TPO_F64, tpo.TPO_F32):
+            assert tpo.tpo_ihelm_sep_variant_for_batch(n, dt, False, 1 << 22) \
+                == tpo.tpo_ihelm_sep_variant_for(n, dt)
     assert tpo.tpo_ihelm_sep_variant_for(17, tpo.TPO_F64) == tpo.TPO_ERR_UNSUPPORTED
     assert tpo.tpo_ihelm_sep_variant_for(0, tpo.TPO_F32) == tpo.TPO_ERR_INVALID_ARG
 

@@ -133,11 +133,14 @@ def test_sep_in_place_ragged_and_status_codes():
     tpo.apply_sep_tensors(*t, v=t[0])                     # v == u
     torch.cuda.synchronize()
     assert oracle.max_rel_err_per_element(t[0].cpu().numpy(), ref) <= 1e-12
-    # the matrix-core tile family has no separable form
+    # a family without a kernel for the type (the 4x4x1 kernels are fp32 only)
     ptrs = [x.data_ptr() for x in t]
     tv = torch.empty_like(t[0])
     rc = tpo.tpo_ihelm_apply_sep_variant(*ptrs, tv.data_ptr(), 7, 45, tpo.TPO_F64, None,
-                                         tpo.TPO_VARIANT_MFMA)
+                                         tpo.TPO_VARIANT_PENCIL_MM)
     assert rc == tpo.TPO_ERR_UNSUPPORTED
+    # every family that has a D form has the separable form too
+    for var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_MFMA):
+        assert tpo.tpo_ihelm_sep_has_variant(7, tpo.TPO_F64, var) == 1
     # E = 0 is a no-op
     assert tpo.tpo_ihelm_apply_sep(*ptrs, tv.data_ptr(), 7, 0, tpo.TPO_F64, None) == tpo.TPO_OK
