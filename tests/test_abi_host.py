@@ -202,7 +202,7 @@ def test_sep_variant_queries():
     for dt in (tpo.TPO_F64, tpo.TPO_F32):
         for n in range(1, tpo.TPO_MAX_N + 1):
             var = tpo.tpo_ihelm_sep_variant_for(n, dt)
-            assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_PENCIL_MM)
+            assert var in (tpo.TPO_VARIANT_PENCIL, tpo.TPO_VARIANT_PENCIL_MM, tpo.TPO_VARIANT_MFMA)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, var)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_AUTO)
             assert tpo.tpo_ihelm_sep_has_variant(n, dt, tpo.TPO_VARIANT_PENCIL)
