@@ -146,8 +146,14 @@ __device__ __forceinline__ void mode_product_mm(const float (&tab)[MmShape<N>::N
 // on every lane; idle lanes carry zeros or stale LDS words and never store.
 // SEP as in ihelm_pencil_kernel: D_e evaluated from lam_x, lam_y, lam_z, mu instead of read
 // (1: IEEE division, 2: hardware reciprocal, 1 ulp).
+// Wavefronts per SIMD the register allocation must leave room for: up to n = 13 the kernel fits
+// 64 registers (eight wavefronts); left to itself the scheduler spends a few more on addresses
+// held across the prologue (71 at n = 13: seven wavefronts, 1 % slower).
+template <int N> constexpr int mm_waves_per_simd() { return N <= 13 ? 8 : 1; }
+
 template <int N, int G, int HINT, bool XCD, int SEP = 0>
 __global__ void __launch_bounds__((PencilShape<float, N, G>::NT))
+__attribute__((amdgpu_waves_per_eu(mm_waves_per_simd<N>())))
 ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float *__restrict__ Sy,
                        const float *__restrict__ Sz, const float *__restrict__ D, float *v,
                        long long num_elems, const float *__restrict__ lam_x,
@@ -163,19 +169,28 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int g = tid / P;
-    const int p = tid - g * P;
-    const int hi = p / N;
-    const int lo = p - hi * N;
     const long long nbatch = (num_elems + G - 1) / G;
     const long long batch = pencil_batch<XCD>(nbatch);
     if (XCD && batch >= nbatch) return;
+    const int g_ = tid / P;
+    const bool on = (tid < G * P) && (batch * G + g_ < num_elems);
+    // Lanes without a pencil (past the last pencil of the workgroup, or in element slots past
+    // the end of the field) shadow pencil 0 of the batch's first element: they load what its
+    // lane loads and compute what it computes, and never write.  No branch around the loads,
+    // nothing to initialise for them.
+    const int g = on ? g_ : 0;
+    const int p = on ? tid - g_ * P : 0;
+    const int hi = p / N;
+    const int lo = p - hi * N;
     const long long e = batch * G + g;
-    const bool on = (tid < G * P) && (e < num_elems);
 
-    // Lanes past the last pencil read (never write) slot 0: p < 64 keeps them inside the cube.
-    float *cube = cube_all + (g < G ? g : 0) * CUBE;
-    const size_t base = (size_t)(on ? e : 0) * (size_t)(N * N * N);
+    float *cube = cube_all + g * CUBE;
+    // addresses: one base per workgroup (uniform) plus a 32-bit word offset per lane
+    constexpr int N3 = N * N * N;
+    const size_t wg_base = (size_t)(batch * G) * (size_t)N3;
+    const char *ub = reinterpret_cast<const char *>(u + wg_base);
+    char *vb = reinterpret_cast<char *>(v + wg_base);
+    const int off_bc = (g * N3 + p) * 4;             // byte offset of word (l = 0, b, c) of the lane's element
 
     float x[N], y[NY], dd[N];
     float tab[M::NTAB];
@@ -184,24 +199,21 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     // forward, axis 0: lane (b,c) = (hi,lo)
 #pragma unroll
     for (int t = 0; t < M::NTAB; ++t) tab[t] = mm_coef<N>(Sx, true, t, lane);
-    if (on) {
 #pragma unroll
-        for (int l = 0; l < N; ++l) x[l] = gload<(HINT & 1) != 0>(u + base + (size_t)(l * P + p));
-        if constexpr (SEP != 0) {
-            sep_ab = lam_x[hi] + lam_y[lo];
-            sep_mu = mu[e];
-        } else {
-            load_words<(HINT & 4) != 0>(D + base + (size_t)(p * N), dd);
-        }
+    for (int l = 0; l < N; ++l)
+        x[l] = gload<(HINT & 1) != 0>(reinterpret_cast<const float *>(ub + (off_bc + l * P * 4)));
+    if constexpr (SEP != 0) {
+        sep_ab = lam_x[hi] + lam_y[lo];
+        sep_mu = mu[e];
     } else {
-#pragma unroll
-        for (int l = 0; l < N; ++l) { x[l] = 0.0f; dd[l] = 0.0f; }
+        load_words<(HINT & 4) != 0>(D + wg_base + (unsigned)(g * N3 + p * N), dd);
     }
     {
         using Stage = MmStage<N, Sh::NT / 64>;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: table choice per wavefront
         float val[Stage::PER_WAVE];
-        Stage::load(Sx, Sy, Sz, tid >> 6, lane, val);
-        Stage::store(tabs, tid >> 6, lane, val);
+        Stage::load(Sx, Sy, Sz, wave, lane, val);
+        Stage::store(tabs, wave, lane, val);
     }
     mode_product_mm<N, true>(tab, (const TPO_CONSTANT float *)Sx, x, y);
     if (on) {
@@ -259,7 +271,8 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     mode_product_mm<N, false>(tab, (const TPO_CONSTANT float *)Sx, x, y);
     if (on) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) gstore<(HINT & 2) != 0>(v + base + (size_t)(i * P + p), y[i]);
+        for (int i = 0; i < N; ++i)
+            gstore<(HINT & 2) != 0>(reinterpret_cast<float *>(vb + (off_bc + i * P * 4)), y[i]);
     }
 }
 
