@@ -22,6 +22,7 @@ import argparse
 import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -75,13 +76,16 @@ KERNEL_SOURCES = {
 
 
 def kernel_source_hash(op: str = "ihelm") -> str:
-    """Hash of the sources an operation's kernels are built from; ties stored HBM-traffic
-    counters to the code they measured."""
+    """Hash of the code an operation's kernels are built from (comments and layout left out: they
+    do not change the kernel); ties stored HBM-traffic counters to the code they measured."""
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2604_19906_amd", "csrc")
     for name in sorted(KERNEL_SOURCES[op]):
+        text = open(os.path.join(csrc, name), encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
         h.update(name.encode())
-        h.update(open(os.path.join(csrc, name), "rb").read())
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

@@ -184,9 +184,9 @@ convection_pencil_kernel(const T *__restrict__ Pq, const T *__restrict__ Mq, con
 
 // fp32 form with the mode products issued as 4x4x1 matrix-core outer products
 // (tpo_pencil_mm.hpp): same data movement; the coefficient tables of D and I (both used
-// untransposed) stay in registers for the whole kernel.  The matrix instructions ignore the
-// execution mask, so they run on every lane; idle lanes carry zeros or stale LDS words and
-// never store.
+// untransposed) stay in registers for the whole kernel.  The matrix instructions run on whole
+// wavefronts, outside the `on` branches (their broadcast coefficients come from active lanes
+// only); idle lanes carry zeros or stale LDS words and never store.
 template <int N, int G, int HINT, bool XCD, bool SPLIT = false>
 __global__ void __launch_bounds__((PencilShape<float, N, G>::NT))
 convection_mm_kernel(const float *__restrict__ Pq, const float *__restrict__ Mq,

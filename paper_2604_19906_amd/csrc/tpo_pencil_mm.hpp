@@ -142,8 +142,10 @@ __device__ __forceinline__ void mode_product_mm(const float (&tab)[MmShape<N>::N
 }
 
 // HINT and XCD as in ihelm_pencil_kernel; D_e is always loaded in its pencil layout.
-// The matrix instructions ignore the execution mask, so they run outside the `on` branches
-// on every lane; idle lanes carry zeros or stale LDS words and never store.
+// The matrix instructions run outside the `on` branches, on whole wavefronts: the broadcast
+// coefficient quadruples are read from ACTIVE lanes of the table register only, so a lane that
+// is switched off would take its quadruples away from all the others.  Idle lanes compute on
+// a shadow pencil or stale LDS words and never store.
 // SEP as in ihelm_pencil_kernel: D_e evaluated from lam_x, lam_y, lam_z, mu instead of read
 // (1: IEEE division, 2: hardware reciprocal, 1 ulp).
 // Wavefronts per SIMD the register allocation must leave room for: up to n = 13 the kernel fits

@@ -44,3 +44,21 @@ def test_stored_traffic_needs_a_matching_hash(repo_root):
         else:
             assert got is None
         assert os.path.exists(os.path.join(repo_root, ent["summary"]))
+
+
+def test_kernel_source_hash_follows_code_not_comments(repo_root, tmp_path):
+    """A comment or layout change keeps the hash (the kernel is the same), a code change does not."""
+    import shutil
+
+    b = load_bench(repo_root)
+    want = b.kernel_source_hash("aniso")
+    shutil.copytree(os.path.join(repo_root, "paper_2604_19906_amd", "csrc"),
+                    tmp_path / "paper_2604_19906_amd" / "csrc")
+    b.ROOT = str(tmp_path)
+    assert b.kernel_source_hash("aniso") == want
+    src = tmp_path / "paper_2604_19906_amd" / "csrc" / "tpo_generic.hip"
+    text = src.read_text()
+    src.write_text("// another comment\n/* and a\n   block */\n" + text.replace("\n", "\n\n    ", 3))
+    assert b.kernel_source_hash("aniso") == want
+    src.write_text(text.replace("ANISO_MAX_NT = 256", "ANISO_MAX_NT = 128"))
+    assert b.kernel_source_hash("aniso") != want
