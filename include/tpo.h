@@ -235,17 +235,6 @@ int tpo_convection_apply(const void *P, const void *M, const void *D_vq, const v
  * else 0.  Pure host function. */
 int tpo_convection_has_shape(int n_v, int n_q, int dtype);
 
-/*
- * tpo_stream_scale -- measurement aid, not part of the operator: enqueue the plain streaming
- * kernel v[i] = u[i] * D[i], i < count, over flat DEVICE arrays of `dtype`.  It moves the
- * operator's algorithmic traffic (two reads and one write per word) and nothing else, so the
- * benchmark uses its time as the streaming ceiling and its HBM counters to calibrate those
- * of the operator's kernels.  Pointers must be 16-byte aligned; no aliasing check is made
- * (v == u is fine).  Needs no tpo_create.  Errors: TPO_ERR_INVALID_ARG, TPO_ERR_DEVICE.
- */
-int tpo_stream_scale(const void *u, const void *D, void *v, long long count, int dtype,
-                     void *stream);
-
 /* tpo_status_string -- static, NUL-terminated description of a status; never freed. */
 const char *tpo_status_string(int status);
 

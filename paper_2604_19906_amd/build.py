@@ -1,10 +1,12 @@
-"""Builds libtpo.so (the C-ABI library) for gfx950 with hipcc, in-tree.
+"""Builds libtpo.so (the C-ABI library of the operator) and libtpo_bench.so (the benchmark's
+measurement aid) for gfx950 with hipcc, in-tree.
 
     python -m paper_2604_19906_amd.build          # compile every source and link
 
 Every translation unit under ``csrc/`` is compiled to an object under ``_build/`` (in
-parallel) and linked into ``paper_2604_19906_amd/libtpo.so``.  hipcc cross-compiles for
-gfx950 without a GPU being present.
+parallel).  Those named ``bench_*`` are linked into ``paper_2604_19906_amd/libtpo_bench.so``
+(``include/tpo_bench.h``), all others into ``paper_2604_19906_amd/libtpo.so``
+(``include/tpo.h``).  hipcc cross-compiles for gfx950 without a GPU being present.
 """
 from __future__ import annotations
 
@@ -18,6 +20,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtpo.so")
+BENCH_LIB = os.path.join(HERE, "libtpo_bench.so")
 
 ARCH = "gfx950"
 # Packed-FP32 VALU instructions are switched off for all device code.
@@ -52,14 +55,16 @@ def build(jobs: int = 8, verbose: bool = True) -> str:
     srcs = sources()
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(srcs)))) as ex:
         objs = list(ex.map(_compile, srcs))
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = ["hipcc", "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
-    if verbose:
-        print(f"built {LIB} from {len(srcs)} sources")
+    for lib, part in ((LIB, [o for s_, o in zip(srcs, objs) if not s_.startswith("bench_")]),
+                      (BENCH_LIB, [o for s_, o in zip(srcs, objs) if s_.startswith("bench_")])):
+        tmp = lib + f".tmp{os.getpid()}"
+        cmd = ["hipcc", "--offload-arch=" + ARCH, "-shared", "-fPIC", "-o", tmp] + part
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
+        os.replace(tmp, lib)
+        if verbose:
+            print(f"built {lib} from {len(part)} sources")
     return LIB
 
 

@@ -1,4 +1,4 @@
-// Measurement aid: the plain streaming kernel v[i] = u[i] * D[i] over flat arrays.  It moves
+// Measurement aid (libtpo_bench.so, not the operator library): the plain streaming kernel v[i] = u[i] * D[i] over flat arrays.  It moves
 // exactly the operator's algorithmic traffic (two reads, one write per word) with no other
 // work, so its time is the streaming ceiling the operator is compared with, and the HBM
 // counters it reads calibrate those read for the operator's kernels.
@@ -6,7 +6,7 @@
 
 #include <cstdint>
 
-#include "tpo.h"
+#include "tpo_bench.h"
 #include "tpo_internal.h"
 
 namespace {

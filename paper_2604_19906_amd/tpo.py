@@ -19,7 +19,9 @@ TPO_VARIANT_AUTO, TPO_VARIANT_PENCIL, TPO_VARIANT_MFMA, TPO_VARIANT_PENCIL_MM = 
 TPO_MAX_N = 16
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtpo.so")
+BENCH_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtpo_bench.so")
 _lib = None
+_bench_lib = None
 
 
 class TpoError(RuntimeError):
@@ -69,8 +71,6 @@ def lib():
         l.tpo_convection_apply.restype = ci
         l.tpo_convection_has_shape.argtypes = [ci, ci, ci]
         l.tpo_convection_has_shape.restype = ci
-        l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
-        l.tpo_stream_scale.restype = ci
         l.tpo_status_string.argtypes = [ci]
         l.tpo_status_string.restype = ctypes.c_char_p
         _lib = l
@@ -163,9 +163,24 @@ def tpo_convection_has_shape(n_v: int, n_q: int, dtype: int) -> bool:
     return bool(lib().tpo_convection_has_shape(int(n_v), int(n_q), int(dtype)))
 
 
+def bench_lib():
+    """Load libtpo_bench.so, the benchmark's measurement aid (once).  Raises if it is missing."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            raise RuntimeError(
+                f"{BENCH_LIB_PATH} is missing: build it with `python -m paper_2604_19906_amd.build`")
+        l = ctypes.CDLL(BENCH_LIB_PATH)
+        vp, ci, cll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+        l.tpo_stream_scale.argtypes = [vp, vp, vp, cll, ci, vp]
+        l.tpo_stream_scale.restype = ci
+        _bench_lib = l
+    return _bench_lib
+
+
 def tpo_stream_scale(u, D, v, count, dtype, stream) -> int:
-    """Measurement aid: v[i] = u[i] * D[i] over flat device arrays (streaming ceiling)."""
-    return lib().tpo_stream_scale(u, D, v, int(count), int(dtype), stream)
+    """Measurement aid (libtpo_bench.so): v[i] = u[i] * D[i] over flat device arrays."""
+    return bench_lib().tpo_stream_scale(u, D, v, int(count), int(dtype), stream)
 
 
 def check(status: int, what: str = "tpo call") -> None:

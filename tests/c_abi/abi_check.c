@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "tpo.h"
+#include "tpo_bench.h"
 
 int main(void)
 {

@@ -10,8 +10,8 @@ import pytest
 from paper_2604_19906_amd import tpo
 
 
-def declared_functions(repo_root):
-    text = open(os.path.join(repo_root, "include", "tpo.h")).read()
+def declared_functions(repo_root, header="tpo.h"):
+    text = open(os.path.join(repo_root, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tpo_[a-z_0-9]+)\s*\(", text)))
 
@@ -22,6 +22,13 @@ def test_library_exports_every_declared_symbol(repo_root):
     l = tpo.lib()
     for name in names:
         assert hasattr(l, name), f"{name} declared in tpo.h but not exported"
+    # every header under include/ has its library: the measurement aid lives in its own
+    assert sorted(os.listdir(os.path.join(repo_root, "include"))) == ["tpo.h", "tpo_bench.h"]
+    aid = declared_functions(repo_root, "tpo_bench.h")
+    assert aid == ["tpo_stream_scale"]
+    for name in aid:
+        assert hasattr(tpo.bench_lib(), name), f"{name} declared in tpo_bench.h but not exported"
+        assert not hasattr(l, name), f"{name} belongs to libtpo_bench.so, not to the operator library"
 
 
 def test_status_strings():
