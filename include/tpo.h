@@ -125,7 +125,8 @@ int tpo_ihelm_variant_for(int n, int dtype, int shared_s);
 
 /* tpo_ihelm_variant_for_batch -- the family TPO_VARIANT_AUTO selects for a call with
  * num_elems elements (the paper times 8192 elements per call, Sec. 6.1; with a few thousand
- * workgroups per launch another family can be ahead of the large-batch choice).  Arguments,
+ * workgroups per launch another family can be ahead of the large-batch choice; with the
+ * kernels as they stand the answer is the same for every num_elems).  Arguments,
  * return values and errors as tpo_ihelm_variant_for; num_elems < 0 is TPO_ERR_INVALID_ARG.
  * Pure host function; needs no device. */
 int tpo_ihelm_variant_for_batch(int n, int dtype, int shared_s, long long num_elems);

@@ -19,14 +19,13 @@ int auto_variant(int n, int dtype, bool shared_s, long long num_elems)
 {
     // Measured on MI355X at the sizes of the named workloads (ms per launch, pencil / MFMA):
     // fp64 n=8 0.25 / 0.27, n=11 1.46 / 1.69, fp32 n=13 5.99 / 6.09: pencil.
-    // fp64 n=16: pencil 1.19; MFMA 1.16 when one matrix is shared by the three directions
-    // (A operands held once: 130 instead of 162 VGPRs), 1.29 with three distinct matrices.
-    // Between about 3000 and 12000 elements the pencil kernel is ahead there (E = 4096: 75.6
-    // against 79.3 us, 8192: 139 against 145; E = 2048: 46.6 against 38.3, from 16384 on the
-    // matrix-core kernel leads again): the launch is a few rounds of resident workgroups, and
-    // the pencil kernel's rounds (4 workgroups per CU against 3) divide such batches better.
-    if (dtype == TPO_F64 && n == 16 && shared_s)
-        return (num_elems > 3072 && num_elems <= 12288) ? TPO_VARIANT_PENCIL : TPO_VARIANT_MFMA;
+    // fp64 n=16: pencil 1.16-1.23; MFMA 1.13-1.17 when one matrix is shared by the three
+    // directions (A operands held once: 134 instead of 156 VGPRs), 1.21 with three distinct
+    // matrices.  With a shared matrix the matrix-core kernel leads at every batch size (us per
+    // launch, pencil / MFMA: E = 1024 26.2 / 22.1, 2048 46.2 / 36.4, 4096 80.9 / 77.1, 8192 148.5 /
+    // 145.4, 12288 236 / 220, 16384 311 / 292), so the choice does not depend on num_elems.
+    (void)num_elems;
+    if (dtype == TPO_F64 && n == 16 && shared_s) return TPO_VARIANT_MFMA;
     // fp32: with 4x4x1 matrix-core products the pencil kernel leaves the vector-FMA bound
     // (n=13, E=1048576: 5.5 against 6.0 ms).  All three families on 1 GiB fields, every n, each at
     // its best setting (GB/s, vector-FMA pencil / 4x4x1 pencil / MFMA tiles): n=8 6079/5853/4790,

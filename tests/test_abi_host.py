@@ -251,7 +251,7 @@ def test_variant_queries():
             for shared in (False, True):
                 assert tpo.tpo_ihelm_variant_for_batch(n, dt, shared, 1 << 22) \
                     == tpo.tpo_ihelm_variant_for(n, dt, shared)
-    assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, True, 8192) == tpo.TPO_VARIANT_PENCIL
+    assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, True, 8192) == tpo.TPO_VARIANT_MFMA
     assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, True, 65536) == tpo.TPO_VARIANT_MFMA
     assert tpo.tpo_ihelm_variant_for_batch(16, tpo.TPO_F64, False, 8192) == tpo.TPO_VARIANT_PENCIL
     assert tpo.tpo_ihelm_variant_for_batch(4, tpo.TPO_F64, True, -1) == tpo.TPO_ERR_INVALID_ARG
