@@ -90,8 +90,8 @@ struct MfmaShape {
 // one is being computed, so that no workgroup ever sits idle waiting for its first loads.
 // WAVES: wavefronts per SIMD the register allocation must leave room for (1 = no demand).
 // SAMES = true: the caller passed one matrix for all three directions (equal pointers); the A
-// operands are then held once instead of three times (for n = 16 in fp64 that is 32 VGPRs,
-// the difference between three and four wavefronts per SIMD).
+// operands are then held once instead of three times (n = 16 in fp64: 134 instead of 156
+// VGPRs, 1.15 against 1.21 ms on 65536 elements).
 // SEP != 0: D is not read; every lane evaluates the D_e entries of its accumulator layout from
 // the separable form 1 / (((lam_x[a] + lam_y[b]) + lam_z[c]) + mu[e]) (SEP = 1: IEEE division,
 // 2: recip_<false>) where the D form loads them; D is ignored and may be null.
