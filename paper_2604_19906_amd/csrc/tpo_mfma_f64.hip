@@ -16,16 +16,18 @@ struct MfmaTune_f64 {
     static constexpr bool XCD = false;
 };
 
-// n = 16: one workgroup per element, plain loads and stores (1.13-1.17 ms on 65536 elements
-// with a shared matrix; the persistent form measured 0.08 ms slower there).
+// n = 16: one workgroup per element, non-temporal stores (on the named workload, alternating
+// libraries on one box: 1.115-1.118 ms against 1.139 with cached stores, 1.128 with non-temporal
+// loads as well, 1.156 with non-temporal loads only; also ahead on small batches: E = 4096 68.7
+// against 76.8 us, 8192 143 against 146; the persistent form measured 0.08 ms slower).
 template <>
 struct MfmaTune_f64<16> {
     static constexpr int G = 1;
     static constexpr int NW = 4;
-    static constexpr int HINT = 0;
+    static constexpr int HINT = 2;
     static constexpr bool PERSIST = false;
-    static constexpr int WAVES = 1;     // asking for a fourth wavefront per SIMD (125 VGPRs) measured equal
-    static constexpr bool XCD = false;  // die renumbering measured equal (1.280 against 1.282 ms)
+    static constexpr int WAVES = 1;     // asking for a fourth wavefront per SIMD: 1.127 against 1.117 ms
+    static constexpr bool XCD = false;  // die renumbering: 1.123 against 1.117 ms
 };
 // n = 11: persistent grid with register prefetch of the next element (1.69 ms against 1.87 ms).
 template <>

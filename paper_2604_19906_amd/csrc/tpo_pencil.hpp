@@ -320,7 +320,9 @@ ihelm_pencil_kernel(const T *u, const T *Sx_, const T *Sy_, const T *Sz_,
 // its pencil layout, half the LDS; 0: coalesced and parked in LDS), and whether the workgroups
 // are renumbered per accelerator die.  One row per n = 1..16: the best of a sweep on MI355X over
 // G in {1,2,3,4,6,8,12,16,32} x hint bits x D mode x renumbering on 1 GiB fields; n = 8, 11
-// (fp64) and 13 (fp32) are the sweeps at the sizes of the named workloads.  n = 1 keeps the
+// (fp64) and 13 (fp32) are the sweeps at the sizes of the named workloads, re-checked on the
+// named workloads' own data (n = 8: D_e in per-lane runs 0.2501-0.2506 ms against 0.2523-0.2550
+// parked in LDS, at 4 elements per workgroup with non-temporal accesses).  n = 1 keeps the
 // lane-utilisation rule (G = 0 in the table).
 struct PencilRow { int g, hint, ddirect, xcd; };
 template <typename T> struct PencilTable;
@@ -328,7 +330,7 @@ template <> struct PencilTable<double> {
     static constexpr PencilRow row[TPO_MAX_N + 1] = {
         {0, 2, 1, 0},
         {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {4, 3, 0, 0},  {16, 0, 1, 0}, {1, 3, 1, 0},
-        {1, 3, 1, 0},  {4, 3, 0, 0},  {2, 0, 1, 0},  {1, 3, 1, 0},  {1, 0, 1, 1},  {3, 3, 1, 0},
+        {1, 3, 1, 0},  {4, 3, 1, 0},  {2, 0, 1, 0},  {1, 3, 1, 0},  {1, 0, 1, 1},  {3, 3, 1, 0},
         {3, 0, 1, 0},  {1, 0, 1, 0},  {1, 0, 1, 0},  {1, 3, 1, 1},
     };
 };
@@ -349,12 +351,18 @@ struct PencilTune {
     static constexpr bool XCD = R.xcd != 0;
     static constexpr size_t LDS_MIN = 0;    // LDS requested at least (caps workgroups per CU)
 };
-// n = 11: asking for 18 KB of LDS (10.4 KB are used) holds the CU at 8 workgroups instead of
-// 12; with fewer loads in flight the memory system runs 1.5 % faster (1.437 against 1.463 ms).
+// n = 11: two elements per workgroup (242 of 256 lanes), non-temporal loads of u_e, and an LDS
+// request of 28 KB (20.8 KB are used), which holds the CU at 5 workgroups = 10 elements instead
+// of 7: with fewer loads in flight the memory system runs faster.  Chosen on the named workload
+// (E = 262144, full-mantissa values; the settings rank differently on low-entropy data, where
+// the clock runs higher), alternating libraries on one box, ms per launch: this setting 1.421-
+// 1.424; the same with cached u_e loads 1.450-1.452; 26 KB / 30 KB requests 1.465 / 1.421-1.430;
+// one element per workgroup with 18 KB (the earlier choice) 1.441-1.462, with 14 KB 1.469;
+// three / four elements per workgroup 1.518 / 1.472.
 template <> struct PencilTune<double, 11> {
-    static constexpr int G = 1, HINT = 0;
+    static constexpr int G = 2, HINT = 1;
     static constexpr bool DDIRECT = true, XCD = true;
-    static constexpr size_t LDS_MIN = 18 * 1024;
+    static constexpr size_t LDS_MIN = 28 * 1024;
 };
 
 // Settings for small batches, used when LO < num_elems <= HI (HI = 0: never).  With a few
@@ -362,9 +370,11 @@ template <> struct PencilTune<double, 11> {
 // divide the batch and how fast a round drains count for more than the steady-state memory
 // behaviour the large-batch settings were chosen for.  From sweeps over E = 2048 .. 131072 on
 // MI355X (the batch of 8192 elements per call is the one the paper times, Sec. 6.1):
-//  * n = 11: up to 65536 elements the die renumbering and the occupancy cap cost more than they
-//    save (E = 4096: 25.3 against 27.8 us, 16384: 97.6 against 101.2, 32768: 189 against 196,
-//    65536: 374 against 377; from 98304 on the large-batch settings are ahead again);
+//  * n = 11: up to 6144 elements one element per workgroup without die renumbering and occupancy
+//    cap is ahead (us per launch, against the large-batch settings: E = 1024 10.9 / 11.3, 4096
+//    27.0 / 29.0, 6144 38.4 / 38.4); beyond, the two leapfrog with the number of rounds of
+//    resident workgroups (8192 49.2 / 47.2, 12288 74.0 / 67.0, 16384 97.8 / 99.7, 24576 142.3 /
+//    142.3, 49152 277 / 281, 65536 368.5 / 367.1) and the large-batch settings are kept;
 //  * n = 8: between 4096 and 24576 elements one element per workgroup with cached accesses and
 //    D_e in its pencil layout beats four per workgroup (8192: 19.5 against 20.5 us, 16384: 33.2
 //    against 35.9); at 4096 and from 32768 on the large-batch settings win.
@@ -373,9 +383,10 @@ struct PencilSmallTune : PencilTune<T, N> {
     static constexpr long long LO = 0, HI = 0;
 };
 template <> struct PencilSmallTune<double, 11> : PencilTune<double, 11> {
+    static constexpr int G = 1, HINT = 0;
     static constexpr bool XCD = false;
     static constexpr size_t LDS_MIN = 0;
-    static constexpr long long LO = 0, HI = 65536;
+    static constexpr long long LO = 0, HI = 6144;
 };
 template <> struct PencilSmallTune<double, 8> : PencilTune<double, 8> {
     static constexpr int G = 1, HINT = 0;
@@ -390,6 +401,7 @@ template <> struct PencilSmallTune<double, 8> : PencilTune<double, 8> {
 template <typename T, int N>
 struct PencilSepTune : PencilTune<T, N> {};
 template <> struct PencilSepTune<double, 11> : PencilTune<double, 11> {
+    static constexpr int G = 1, HINT = 0;
     static constexpr size_t LDS_MIN = 0;
 };
 template <> struct PencilSepTune<double, 8> : PencilTune<double, 8> {

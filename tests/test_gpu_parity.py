@@ -192,6 +192,35 @@ def test_persistent_mfma_loop_iterates(e):
     assert oracle.max_rel_err_per_element(got, oracle.ihelm_apply(u, sx, sy, sz, d)) <= TOL["f64"]
 
 
+# The launchers switch settings (elements per workgroup, hints, die renumbering) with the batch
+# size: both sides of every switch point, with odd batch sizes so that the last workgroup of the
+# several-elements-per-workgroup settings is ragged; out of place, then in place.
+@pytest.mark.parametrize("n,dtype,name,sizes", [
+    (11, "f64", "pencil", (6144, 6145, 8193, 20011)),
+    (8, "f64", "pencil", (4096, 4097, 24575, 24577)),
+    (13, "f32", "pencil_mm", (262144, 262147)),
+])
+def test_batch_size_dependent_settings(n, dtype, name, sizes):
+    for e in sizes:
+        w = wl.custom(n, e, dtype, key=1500 + n, distinct_s=(dtype == "f32"))
+        print(f"case n={n} {dtype} E={e} variant={name}", flush=True)
+        u, sx, sy, sz, d = wl.make_inputs(w)
+        ref = oracle.ihelm_apply(u, sx, sy, sz, d)
+        tu, td = dev(u), dev(d)
+        if sx is sy and sy is sz:
+            tsx = dev(sx)
+            mats = (tsx, tsx, tsx)
+        else:
+            mats = (dev(sx), dev(sy), dev(sz))
+        v1 = tpo.apply_tensors(tu, *mats, td, variant=VARIANTS[name])
+        torch.cuda.synchronize()
+        err = oracle.max_rel_err_per_element(v1.cpu().numpy(), ref)
+        assert err <= TOL[dtype], f"{w.name} {name}: err {err:.3e}"
+        tpo.apply_tensors(tu, *mats, td, tu, variant=VARIANTS[name])      # v == u
+        torch.cuda.synchronize()
+        assert torch.equal(tu, v1)
+
+
 # small n with millions of elements: many workgroups per launch, several elements per
 # workgroup, a ragged last group; every element checked against the oracle
 @pytest.mark.parametrize("n,dtype,e", [(1, "f64", (1 << 22) + 3), (2, "f32", (1 << 22) + 5),
