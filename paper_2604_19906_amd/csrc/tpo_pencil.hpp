@@ -330,7 +330,7 @@ template <> struct PencilTable<double> {
     static constexpr PencilRow row[TPO_MAX_N + 1] = {
         {0, 2, 1, 0},
         {0, 2, 1, 1},  {16, 0, 1, 0}, {32, 0, 1, 0}, {4, 3, 0, 0},  {16, 0, 1, 0}, {1, 3, 1, 0},
-        {1, 3, 1, 0},  {4, 3, 1, 0},  {2, 0, 1, 0},  {1, 3, 1, 0},  {1, 0, 1, 1},  {3, 3, 1, 0},
+        {1, 3, 1, 0},  {4, 3, 1, 0},  {3, 1, 1, 0},  {1, 3, 1, 0},  {1, 0, 1, 1},  {3, 3, 1, 0},
         {3, 0, 1, 0},  {1, 0, 1, 0},  {1, 0, 1, 0},  {1, 3, 1, 1},
     };
 };
@@ -375,6 +375,10 @@ template <> struct PencilTune<double, 11> {
 //    27.0 / 29.0, 6144 38.4 / 38.4); beyond, the two leapfrog with the number of rounds of
 //    resident workgroups (8192 49.2 / 47.2, 12288 74.0 / 67.0, 16384 97.8 / 99.7, 24576 142.3 /
 //    142.3, 49152 277 / 281, 65536 368.5 / 367.1) and the large-batch settings are kept;
+//  * n = 9 (fp64): three elements per workgroup; non-temporal u_e loads pay from about 30000
+//    elements on (us per launch with / without them: E = 2048 11.6 / 11.1, 8192 28.3 / 27.2, 32768
+//    99.4 / 102.6, 184000 547 / 580; two elements per workgroup with cached loads, the earlier
+//    choice: 11.0, 28.5, 104.0, 569), so they are left out up to 16384 elements;
 //  * n = 8: between 4096 and 24576 elements one element per workgroup with cached accesses and
 //    D_e in its pencil layout beats four per workgroup (8192: 19.5 against 20.5 us, 16384: 33.2
 //    against 35.9); at 4096 and from 32768 on the large-batch settings win.
@@ -387,6 +391,10 @@ template <> struct PencilSmallTune<double, 11> : PencilTune<double, 11> {
     static constexpr bool XCD = false;
     static constexpr size_t LDS_MIN = 0;
     static constexpr long long LO = 0, HI = 6144;
+};
+template <> struct PencilSmallTune<double, 9> : PencilTune<double, 9> {
+    static constexpr int HINT = 0;
+    static constexpr long long LO = 0, HI = 16384;
 };
 template <> struct PencilSmallTune<double, 8> : PencilTune<double, 8> {
     static constexpr int G = 1, HINT = 0;
@@ -406,6 +414,9 @@ template <> struct PencilSepTune<double, 11> : PencilTune<double, 11> {
 };
 template <> struct PencilSepTune<double, 8> : PencilTune<double, 8> {
     static constexpr int G = 1;
+};
+template <> struct PencilSepTune<double, 9> : PencilTune<double, 9> {
+    static constexpr int G = 2, HINT = 0;       // (the D form's retuning at n = 9 was not repeated here)
 };
 
 // SEP: 0 = D read from memory, 1 / 2 = separable diagonal (IEEE division / fast reciprocal).

@@ -198,6 +198,7 @@ def test_persistent_mfma_loop_iterates(e):
 @pytest.mark.parametrize("n,dtype,name,sizes", [
     (11, "f64", "pencil", (6144, 6145, 8193, 20011)),
     (8, "f64", "pencil", (4096, 4097, 24575, 24577)),
+    (9, "f64", "pencil", (16384, 16385)),
     (13, "f32", "pencil_mm", (262144, 262147)),
 ])
 def test_batch_size_dependent_settings(n, dtype, name, sizes):
