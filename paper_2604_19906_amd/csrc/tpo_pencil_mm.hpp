@@ -192,7 +192,15 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     const size_t wg_base = (size_t)(batch * G) * (size_t)N3;
     const char *ub = reinterpret_cast<const char *>(u + wg_base);
     char *vb = reinterpret_cast<char *>(v + wg_base);
-    const int off_bc = (g * N3 + p) * 4;             // byte offset of word (l = 0, b, c) of the lane's element
+    // Byte offset of word (l = MID, b, c) of the lane's element: the n accesses of a pencil along
+    // axis 0 are then this one offset plus immediates (l - MID) * P * 4, all within the +-4 KB an
+    // instruction can carry for n <= 13 (addressed from l = 0 the upper half needs a register
+    // and an add each: 19 vector instructions and 14 registers more per wavefront at n = 13;
+    // 5.44-5.46 against 5.51-5.53 ms on the n = 13 workload).  Opaque to the compiler so that it
+    // keeps this split.
+    constexpr int MID = N / 2;
+    int off_bc = (g * N3 + p + MID * P) * 4;
+    asm volatile("" : "+v"(off_bc));
 
     float x[N], y[NY], dd[N];
     float tab[M::NTAB];
@@ -203,7 +211,7 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     for (int t = 0; t < M::NTAB; ++t) tab[t] = mm_coef<N>(Sx, true, t, lane);
 #pragma unroll
     for (int l = 0; l < N; ++l)
-        x[l] = gload<(HINT & 1) != 0>(reinterpret_cast<const float *>(ub + (off_bc + l * P * 4)));
+        x[l] = gload<(HINT & 1) != 0>(reinterpret_cast<const float *>(ub + off_bc + (l - MID) * P * 4));
     if constexpr (SEP != 0) {
         sep_ab = lam_x[hi] + lam_y[lo];
         sep_mu = mu[e];
@@ -274,7 +282,7 @@ ihelm_pencil_mm_kernel(const float *u, const float *__restrict__ Sx, const float
     if (on) {
 #pragma unroll
         for (int i = 0; i < N; ++i)
-            gstore<(HINT & 2) != 0>(reinterpret_cast<float *>(vb + (off_bc + i * P * 4)), y[i]);
+            gstore<(HINT & 2) != 0>(reinterpret_cast<float *>(vb + off_bc + (i - MID) * P * 4), y[i]);
     }
 }
 
